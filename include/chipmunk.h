@@ -1,0 +1,157 @@
+/*
+ * chipmunk.h - C ABI of the MI355X (gfx950) implementation of the Chipmunk hot
+ * path (arXiv 2506.03275): dynamic column-sparse delta recompute for
+ * Diffusion-Transformer attention and MLP layers.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or synchronises; a call enqueues its kernels on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     returns at once.
+ *   - Tensors are dense and row-major in the layouts stated per call.  bf16
+ *     values are passed as raw uint16_t.  Pointers to bf16/fp32/int32 tensors
+ *     must be 16-byte aligned.
+ *   - Return value: CHIPMUNK_OK, or a negative code; on any error nothing was
+ *     launched.  chipmunk_status_string() gives a text for a code.
+ *   - Index contents (range, duplicates) are preconditions that are not
+ *     checked: every idx entry below its row's count must lie in [0, C).
+ *   - "chunk" = c consecutive tokens that share one set of selected columns
+ *     (the [C,1] column sparsity of Sec. 3.2.1); the last chunk of a sequence
+ *     may hold fewer than c tokens.  NB = ceil(N / c).
+ */
+#ifndef CHIPMUNK_H
+#define CHIPMUNK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CHIPMUNK_OK                0
+#define CHIPMUNK_ERR_NULL         -1  /* a required pointer is NULL */
+#define CHIPMUNK_ERR_SHAPE        -2  /* a size is out of range (<= 0, k > C, k_stride < k, ...) */
+#define CHIPMUNK_ERR_ALIGN        -3  /* a pointer or leading dimension breaks the alignment rule */
+#define CHIPMUNK_ERR_UNSUPPORTED  -4  /* E not in {64,128}, c not in {128,192}, D % 128 or F % 64 != 0, unknown act */
+#define CHIPMUNK_ERR_WORKSPACE    -5  /* workspace missing or too small */
+#define CHIPMUNK_ERR_LAUNCH       -6  /* the HIP runtime refused a launch */
+
+#define CHIPMUNK_ACT_GELU_ERF   0
+#define CHIPMUNK_ACT_GELU_TANH  1
+
+const char* chipmunk_status_string(int32_t status);
+
+/* Voxel token reorder and its inverse (Alg. 1; Sec. 3.2.1).
+ * A sequence holds n_prefix tokens, a T*H*W grid in raster order (t slowest,
+ * w fastest) and n_suffix tokens: N = n_prefix + T*H*W + n_suffix.  After the
+ * reorder every full (vt,vh,vw) voxel occupies vt*vh*vw consecutive positions,
+ * voxels in (tc,hc,wc) order, tokens inside a voxel in (dt,dh,dw) order; grid
+ * positions outside the last full voxel of any dimension follow in raster
+ * order; prefix and suffix tokens keep their places.
+ *   inverse == 0:  dst[b][i]       = src[b][perm[i]]
+ *   inverse != 0:  dst[b][perm[i]] = src[b][i]
+ * src, dst: [batch, N, row_bytes] bytes, must not overlap; both NULL = only
+ * write the permutation.  perm, inv_perm: [N] int32, each may be NULL;
+ * perm[new] = old, inv_perm[old] = new.  row_bytes must be a multiple of 4;
+ * rows that are multiples of 16 bytes with 16-byte aligned src/dst move as
+ * 128-bit words. */
+int32_t chipmunk_voxel_reorder(const void* src, void* dst, int32_t* perm, int32_t* inv_perm,
+                               int batch, int n_prefix, int T, int H, int W, int n_suffix,
+                               int vt, int vh, int vw, int row_bytes, int inverse, void* stream);
+
+/* Per-row top-k column selection (Sec. 3.3.1 idx = TopK_k(D); Sec. 3.3.2 and
+ * Alg. 7 idx = TopK(|T - T_m|)).
+ * cur, prev: [R, ld] fp32 with C used columns (ld >= C, ld % 4 == 0); prev may
+ * be NULL.  score_j = cur_j, or |cur_j - prev_j| in fp32.  The k columns with
+ * the largest score are kept; of equal scores the lower column wins; -0 = +0;
+ * NaN scores are a precondition violation.  idx: [R, k_stride] int32 receives
+ * the kept columns in ascending order in its first k entries (the rest is left
+ * untouched); counts: [R] receives k.  The call is exact, never approximate. */
+int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R, int C, int64_t ld, int k,
+                           int32_t* idx, int32_t* counts, int k_stride, void* stream);
+
+/* Column-sparse delta attention (Sec. 3.3.1 "Sparse Delta Steps"; Alg. 3).
+ * For chunk i of (b,h) with S = idx[b,h,i,0:counts[b,h,i]] and each row n of it:
+ *   out[n] = base[n] + o_scale * softmax_{j in S}(softmax_scale * <q[n],k[j]>) v[j]
+ * The softmax runs over the selected columns only, in fp32, with bf16 MFMA
+ * products accumulated in fp32.  counts == 0 gives out = base.  o_scale = +1
+ * is a sparse step on the cache; o_scale = -1 with base = dense output builds
+ * the cache O_cache of a dense step (Alg. 2).
+ * q, k, v, base, out: [B,H,N,E] bf16; out may alias base.  idx: [B,H,NB,k_stride]
+ * int32; counts: [B,H,NB] int32, each in [0, k_stride].  idx == NULL and
+ * counts == NULL selects every column 0..N-1 (dense attention on the same
+ * kernel; base may then be NULL, meaning zero).
+ * E in {64,128}; c in {128,192}. */
+int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                                   const int32_t* idx, const int32_t* counts,
+                                   const uint16_t* base, uint16_t* out,
+                                   int B, int H, int N, int E, int c, int k_stride,
+                                   float softmax_scale, float o_scale, void* stream);
+
+/* Workspace bytes of chipmunk_attn_dense when column sums are requested (0 on bad arguments). */
+size_t chipmunk_attn_dense_workspace_bytes(int B, int H, int N);
+
+/* Dense attention with exact column sums (Sec. 3.3.1 "Dense Steps"):
+ *   out = softmax(softmax_scale * q k^T) v,
+ *   colsum[b,h,i,j] = sum over the rows n of chunk i of P[b,h,n,j]   (the tensor D).
+ * out: [B,H,N,E] bf16; colsum: [B,H,NB,ld_colsum] fp32 (ld_colsum >= N, multiple
+ * of 4) or NULL.  Normalisers are those of the current step (exact sums, not
+ * the stale-constant approximation of App. B.2): a first pass writes each row's
+ * softmax statistics into ws, a second pass recomputes the scores and sums the
+ * normalised probabilities per chunk.  ws (chipmunk_attn_dense_workspace_bytes)
+ * is needed only when colsum != NULL; its contents are undefined afterwards. */
+int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                            uint16_t* out, float* colsum, int64_t ld_colsum,
+                            int B, int H, int N, int E, int c, float softmax_scale,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace bytes of chipmunk_mlp_tile_mean_preact (0 on bad arguments). */
+size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int c);
+
+/* Token-merged pre-activation (Alg. 7; T_m of Sec. 3.3.2):
+ *   T[b,i,:] = (mean over the rows of chunk i of x[b]) @ w1^T, no bias.
+ * x: [B,N,D] bf16; w1: [F,D] bf16; T: [B,NB,F] fp32.  The chunk mean is formed
+ * in fp32 and fed to the bf16 MFMA as a sum of two bf16 numbers (high and low
+ * part), so T carries about 16 bits of the mean.  D multiple of 128, F of 64.
+ * ws: chipmunk_mlp_tile_mean_workspace_bytes(); contents undefined afterwards. */
+int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16_t* w1, float* T,
+                                      int B, int N, int D, int F, int c,
+                                      void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace bytes of chipmunk_mlp_sparse_delta (0 on bad arguments). */
+size_t chipmunk_mlp_workspace_bytes(int B, int N, int D, int F, int c, int k_stride);
+
+/* Column-sparse delta MLP (Sec. 3.3.2 "Sparse Delta Steps"; App. B.3.1; Alg. 6).
+ * For chunk i of batch b with S = idx[b,i,0:counts[b,i]], each row n and f in S:
+ *   a = act(<x[n], w1[f]> + b1[f]);  delta = a - a_cache[b,f,n];  a_cache[b,f,n] = a
+ *   o_cache[b,n,:] += sum_{f in S} delta * w2[f,:]
+ * a is rounded to bf16 once; that value is stored and used for delta, so that
+ * o_cache = a_cache^T w2 + b2 is preserved up to rounding.  b2 is not added.
+ * x: [B,N,D] bf16; w1, w2: [F,D] bf16; b1: [F] bf16 or NULL; idx: [B,NB,k_stride]
+ * int32 with distinct entries per row; counts: [B,NB]; a_cache: [B,F,a_ld] bf16,
+ * in/out (a_ld >= N, a_ld % 8 == 0); o_cache: [B,N,D] bf16, in/out.
+ * ws: workspace of chipmunk_mlp_workspace_bytes(), contents undefined after.
+ * D multiple of 128, F multiple of 64; c in {128,192}; act as CHIPMUNK_ACT_*.
+ * N*D and F*D must stay below 2^31 elements (32-bit byte offsets inside one
+ * batch row block and inside the weights). */
+int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                                  const uint16_t* w2, const int32_t* idx, const int32_t* counts,
+                                  uint16_t* a_cache, int64_t a_ld, uint16_t* o_cache,
+                                  int B, int N, int D, int F, int c, int k_stride, int act,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/* Dense MLP of a dense step (Sec. 3.3.2 "Dense steps"; Alg. 5):
+ *   a = act(x w1^T + b1) -> a_cache[b,f,n] (bf16, neuron-major);  out = a w2 + b2.
+ * out: [B,N,D] bf16; b2: [D] bf16 or NULL; a_cache: [B,F,a_ld] bf16, written
+ * (required: the second GEMM reads it).  T_m is produced by
+ * chipmunk_mlp_tile_mean_preact on the same x. */
+int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                           const uint16_t* w2, const uint16_t* b2, uint16_t* out,
+                           uint16_t* a_cache, int64_t a_ld,
+                           int B, int N, int D, int F, int c, int act, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHIPMUNK_H */

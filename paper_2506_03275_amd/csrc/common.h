@@ -1,0 +1,95 @@
+// Shared host/device helpers of the gfx950 Chipmunk kernels.  Internal: the
+// public interface is include/chipmunk.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/chipmunk.h"
+
+namespace chipmunk {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define CHIPMUNK_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define CHIPMUNK_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+
+// two floats -> packed bf16 pair (round to nearest even), lo in bits 0..15
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Asynchronous 16-byte load from global memory straight into LDS: lane l of the
+// wave deposits its 16 bytes at lds_wave_base + 16*l (lds_wave_base is a
+// wave-uniform LDS byte address).  The global address is base + byte_offset
+// with a per-lane 32-bit offset, which makes this a gather.  Completion is
+// counted by vmcnt; the caller waits (wait_all_memory) before the barrier that
+// publishes the tile.  Issued as inline assembly so that the compiler does not
+// serialise later LDS reads of OTHER buffers behind the outstanding transfer.
+__device__ __forceinline__ void load_global_to_lds_16B(const void* base, uint32_t byte_offset,
+                                                       uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_wave_base), "v"(byte_offset), "s"(base)
+                 : "memory");
+}
+
+// LDS byte address of a __shared__ object, made wave-uniform
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)CHIPMUNK_LDS_PTR(p));
+}
+
+// Transposing LDS read of 16-bit elements.  Within each block of 16 lanes,
+// lane i supplies the address of 4 consecutive elements: row i/4, columns
+// 4*(i%4)..+3 of a 4x16 block; lane j receives column j of that block, i.e.
+// element t of its result is the block's (row t, column j).
+__device__ __forceinline__ short4v lds_read_tr16(const void* lds_ptr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) short4v*)(lds_ptr));
+}
+
+// max / sum over the four 16-lane rows of a wave, result in every lane
+__device__ __forceinline__ float rows4_max(float x) {
+    uint32_t u = __float_as_uint(x);
+    auto s = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = fmaxf(__uint_as_float(s[0]), __uint_as_float(s[1]));
+    u = __float_as_uint(x);
+    auto t = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(t[0]), __uint_as_float(t[1]));
+}
+__device__ __forceinline__ float rows4_sum(float x) {
+    uint32_t u = __float_as_uint(x);
+    auto s = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = __uint_as_float(s[0]) + __uint_as_float(s[1]);
+    u = __float_as_uint(x);
+    auto t = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(t[0]) + __uint_as_float(t[1]);
+}
+
+__device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
+
+// ---- host side ---------------------------------------------------------------
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int32_t launch_status() {
+    return hipGetLastError() == hipSuccess ? CHIPMUNK_OK : CHIPMUNK_ERR_LAUNCH;
+}
+
+}  // namespace chipmunk

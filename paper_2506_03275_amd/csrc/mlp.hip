@@ -1,0 +1,605 @@
+// Column-sparse delta MLP (Sec. 3.3.2 "Sparse Delta Steps", App. B.3.1, Alg. 6),
+// the dense MLP of a dense step (Alg. 5) and the token-merged pre-activation
+// (Alg. 7) for gfx950.
+//
+// GEMM1  pre[tok, s] = <x[tok], w1[idx[s]]>: one workgroup owns (token chunk,
+//        128 selected neurons).  The x tile and the gathered w1 rows stream
+//        through LDS (asynchronous 16-byte loads, double buffered, K tile 64)
+//        into bf16 MFMA 32x32x16.  Epilogue: bias, activation, rounding to
+//        bf16, a transpose through LDS to the neuron-major layout of a_cache,
+//        then per 8 consecutive tokens of one neuron: read the cached
+//        activation, write the new one, write delta^T to the workspace.  Each
+//        (chunk, neuron) cell has one writer: no atomics.
+// GEMM2  o_cache[tok, :] += sum_s delta[tok, s] * w2[idx[s], :]: one workgroup
+//        owns (token chunk, 128 output columns) and walks the selected rows in
+//        tiles of 64.  Both operands are stored with the contraction index as
+//        the slow axis (delta^T rows, w2 rows), so both come out of LDS through
+//        the transposing 64-bit read.  Epilogue: fp32 tile through LDS, add to
+//        the cached output in fp32, round once, store in 256-byte runs.
+// The dense MLP is the same two kernels with "every neuron selected": GEMM1
+// writes a_cache only and GEMM2 reads its A operand from a_cache and adds b2.
+#include "common.h"
+
+namespace chipmunk {
+
+constexpr int kBN = 128;  // neurons (GEMM1) or output columns (GEMM2) per workgroup
+constexpr int kBK = 64;   // contraction tile
+
+enum Gemm1Mode { kSparseDelta = 0, kDenseAct = 1, kPlainF32 = 2 };
+
+__device__ __forceinline__ float gelu(float x, int act) {
+    if (act == CHIPMUNK_ACT_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
+    // tanh form: 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
+    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return x / (1.f + __builtin_amdgcn_exp2f(-2.885390081777927f * u));
+}
+
+struct Gemm1Params {
+    const uint16_t* x;       // [B, N, ldx] rows of K elements
+    const uint16_t* w1;      // [F, D]
+    const uint16_t* b1;      // [F] or null
+    const int32_t* idx;      // [units, k_stride] or null (dense)
+    const int32_t* counts;   // [units] or null
+    uint16_t* a_cache;       // [B, F, a_ld]
+    uint16_t* delta_t;       // workspace [units, k_pad, BM]
+    float* out_f32;          // kPlainF32: [B*N, F]
+    int64_t a_ld;
+    int N, NB, D, F, K, ldx; // K = contraction length (D, or 2D for the split-precision scores GEMM)
+    int k_stride, k_pad, act;
+};
+
+template <int BM, int MODE>
+__global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
+    constexpr int MT = BM / 64;                    // 32-row MFMA tiles per wave (wave tile = BM/2 x 64)
+    constexpr int XT = BM * 128;                   // bytes of the x tile  [BM][64] bf16
+    constexpr int WT = kBN * 128;                  // bytes of the w1 tile [128][64] bf16
+    constexpr int STAGE = XT + WT;
+    constexpr int NIX = BM / 32;                   // 16-byte loads per lane for the x tile
+    constexpr int NIW = kBN / 32;
+    constexpr int TS = BM * 2 + 16;                // row stride of the transposed epilogue tile
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    __shared__ int32_t s_neuron[kBN];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    const int unit = blockIdx.y;                   // (batch, token chunk)
+    const int b = unit / p.NB, chunk = unit % p.NB;
+    const int row0 = chunk * BM;
+    const int col0 = blockIdx.x * kBN;
+    const int count = p.counts ? p.counts[unit] : p.F;
+    if (col0 >= count && MODE != kSparseDelta) return;
+    if (MODE == kSparseDelta && col0 >= ((count + kBK - 1) / kBK) * kBK) return;  // nothing to compute or to zero
+
+    // neuron of each of the 128 columns of this tile (clamped: columns at or beyond count
+    // compute a duplicate that is never stored)
+    if (tid < kBN) {
+        int s = col0 + tid;
+        int last = max(count - 1, 0);
+        int f = p.idx ? p.idx[(int64_t)unit * p.k_stride + min(s, last)] : min(s, last);
+        s_neuron[tid] = f;
+    }
+    __syncthreads();
+
+    // per-lane source offsets (bytes) of the asynchronous tile loads; the K offset is uniform
+    uint32_t xoff[NIX], woff[NIW];
+#pragma unroll
+    for (int i = 0; i < NIX; i++) {
+        int row = (i * 4 + w) * 8 + (lane >> 3);
+        int chunk16 = (lane & 7) ^ ((row >> 1) & 7);
+        int tok = min(row0 + row, p.N - 1);
+        xoff[i] = (uint32_t)tok * (uint32_t)(p.ldx * 2) + chunk16 * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < NIW; i++) {
+        int row = (i * 4 + w) * 8 + (lane >> 3);
+        int chunk16 = (lane & 7) ^ ((row >> 1) & 7);
+        woff[i] = (uint32_t)s_neuron[row] * (uint32_t)(p.D * 2) + chunk16 * 16;
+    }
+    const uint16_t* xb = p.x + (int64_t)b * p.N * p.ldx;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
+
+    auto issue = [&](int kt, int stage) {
+        const uint16_t* xs = xb + kt * kBK;
+        const uint16_t* ws = p.w1 + (kt * kBK) % p.D;   // the scores GEMM walks w1's row twice (hi and lo halves of A)
+#pragma unroll
+        for (int i = 0; i < NIX; i++) load_global_to_lds_16B(xs, xoff[i], lds0 + stage * STAGE + i * 4096);
+#pragma unroll
+        for (int i = 0; i < NIW; i++) load_global_to_lds_16B(ws, woff[i], lds0 + stage * STAGE + XT + i * 4096);
+    };
+
+    f32x16 acc[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
+
+    // LDS read offsets: row l32 of a 32-row tile, 16-byte chunk (2*ks + h) ^ swizzle(row)
+    const int sw = (l32 >> 1) & 7;
+    const int aoff = (wm * (BM / 2) + l32) * 128 + ((h ^ sw) * 16);
+    const int boff = XT + (wn * 64 + l32) * 128 + ((h ^ sw) * 16);
+
+    const int ktiles = p.K / kBK;
+    issue(0, 0);
+    for (int kt = 0; kt < ktiles; kt++) {
+        const int stage = kt & 1;
+        wait_all_memory();
+        __syncthreads();
+        if (kt + 1 < ktiles) issue(kt + 1, stage ^ 1);
+        const uint8_t* sb = smem + stage * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            bf16x8 bop[2];
+#pragma unroll
+            for (int nt = 0; nt < 2; nt++)
+                bop[nt] = *reinterpret_cast<const bf16x8*>(sb + nt * 32 * 128 + (boff ^ (32 * ks)));
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                bf16x8 aop = *reinterpret_cast<const bf16x8*>(sb + mt * 32 * 128 + (aoff ^ (32 * ks)));
+#pragma unroll
+                for (int nt = 0; nt < 2; nt++)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nt], acc[mt][nt], 0, 0, 0);
+            }
+        }
+    }
+
+    if (MODE == kPlainF32) {
+        // out[row, col] fp32; a lane holds one column and 4 consecutive rows per register group
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int nt = 0; nt < 2; nt++) {
+                int col = col0 + wn * 64 + nt * 32 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    int row = row0 + wm * (BM / 2) + mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                    if (row < p.N && col < p.F) p.out_f32[((int64_t)b * p.N + row) * p.F + col] = acc[mt][nt][r];
+                }
+            }
+        return;
+    }
+
+    // ---- epilogue: bias, activation, bf16, transpose to [neuron][token] through LDS ----
+    __syncthreads();  // every wave is done with the stage buffers
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) {
+        int nl = wn * 64 + nt * 32 + l32;
+        float bias = p.b1 ? bf16_bits_to_float(p.b1[s_neuron[nl]]) : 0.f;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int rg = 0; rg < 4; rg++) {
+                int tl = wm * (BM / 2) + mt * 32 + rg * 8 + h * 4;
+                float a0 = gelu(acc[mt][nt][rg * 4 + 0] + bias, p.act);
+                float a1 = gelu(acc[mt][nt][rg * 4 + 1] + bias, p.act);
+                float a2 = gelu(acc[mt][nt][rg * 4 + 2] + bias, p.act);
+                float a3 = gelu(acc[mt][nt][rg * 4 + 3] + bias, p.act);
+                u32x2 v = {pack_bf16x2(a0, a1), pack_bf16x2(a2, a3)};
+                *reinterpret_cast<u32x2*>(smem + nl * TS + tl * 2) = v;
+            }
+    }
+    __syncthreads();
+    constexpr int CPR = BM / 8;  // 16-byte chunks (8 tokens) per neuron row
+    for (int item = tid; item < kBN * CPR; item += 256) {
+        int nl = item / CPR, ch = item - nl * CPR;
+        int s = col0 + nl;
+        int tok0 = row0 + ch * 8;
+        int nvalid = min(8, p.N - tok0);
+        if (nvalid <= 0) {
+            if (MODE == kSparseDelta && s < p.k_pad)
+                *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = u32x4{0, 0, 0, 0};
+            continue;
+        }
+        if (s >= count) {  // padding rows of the contraction must read as zero in GEMM2
+            if (MODE == kSparseDelta && s < p.k_pad)
+                *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = u32x4{0, 0, 0, 0};
+            continue;
+        }
+        u32x4 a8 = *reinterpret_cast<const u32x4*>(smem + nl * TS + ch * 16);
+        uint16_t* arow = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + tok0;
+        if (MODE == kDenseAct) {
+            if (nvalid == 8) {
+                *reinterpret_cast<u32x4*>(arow) = a8;
+            } else {
+                for (int e = 0; e < nvalid; e++) arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
+            }
+            continue;
+        }
+        u32x4 old8 = u32x4{0, 0, 0, 0};
+        if (nvalid == 8) {
+            old8 = *reinterpret_cast<const u32x4*>(arow);
+            *reinterpret_cast<u32x4*>(arow) = a8;
+        } else {
+            for (int e = 0; e < nvalid; e++) {
+                old8[e >> 1] |= (uint32_t)arow[e] << (16 * (e & 1));
+                arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        u32x4 d8;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; e2++) {
+            float dlo = bf16_bits_to_float(a8[e2] & 0xffffu) - bf16_bits_to_float(old8[e2] & 0xffffu);
+            float dhi = bf16_bits_to_float(a8[e2] >> 16) - bf16_bits_to_float(old8[e2] >> 16);
+            if (2 * e2 >= nvalid) dlo = 0.f;
+            if (2 * e2 + 1 >= nvalid) dhi = 0.f;
+            d8[e2] = pack_bf16x2(dlo, dhi);
+        }
+        *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = d8;
+    }
+}
+
+struct Gemm2Params {
+    const uint16_t* a_t;     // sparse: delta^T workspace [units, k_pad, BM]; dense: a_cache [B, F, a_ld]
+    const uint16_t* w2;      // [F, D]
+    const uint16_t* bias;    // dense: b2 [D] or null
+    const int32_t* idx;      // [units, k_stride] or null
+    const int32_t* counts;   // [units] or null
+    uint16_t* o;             // sparse: o_cache in/out; dense: out
+    int64_t a_ld;
+    int N, NB, D, F, k_stride, k_pad;
+    int dense;
+};
+
+template <int BM>
+__device__ __forceinline__ int swizzle_at(int row) {  // for rows of BM tokens (BM*2 bytes)
+    if (BM == 192) return (row & 2) << 1;
+    return ((row & 3) << 2) | ((row >> 2) & 3);
+}
+__device__ __forceinline__ int swizzle_w2(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+template <int BM>
+__global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
+    constexpr int MT = BM / 64;
+    constexpr int RBA = BM * 2;                    // bytes per row of the A^T tile
+    constexpr int CPA = BM / 8;                    // 16-byte chunks per A^T row
+    constexpr int AT = kBK * RBA;                  // A^T tile bytes [64][BM]
+    constexpr int WT = kBK * 256;                  // w2 tile bytes  [64][128]
+    constexpr int STAGE = AT + WT;
+    constexpr int NIA = kBK * CPA / 256;           // loads per lane, A^T tile
+    constexpr int NIW = kBK * 16 / 256;            // loads per lane, w2 tile
+    constexpr int CS = 128 * 4 + 32;               // row stride (bytes) of the fp32 epilogue tile
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    const int l16 = lane & 15, mb = (lane >> 4) & 1, h = lane >> 5;
+
+    const int unit = blockIdx.y;
+    const int b = unit / p.NB, chunk = unit % p.NB;
+    const int row0 = chunk * BM;
+    const int d0 = blockIdx.x * kBN;
+    const int count = p.counts ? p.counts[unit] : p.F;
+    if (count <= 0 && !p.dense) return;            // nothing selected: the cache stays as it is
+    const int32_t* idxp = p.idx ? p.idx + (int64_t)unit * p.k_stride : nullptr;
+    const int ktiles = (count + kBK - 1) / kBK;
+
+    // A^T source: row (selected slot or neuron) -> tokens of this chunk
+    const uint16_t* abase;
+    int64_t a_row_stride;                          // elements between consecutive contraction rows
+    if (p.dense) {
+        abase = p.a_t + (int64_t)b * p.F * p.a_ld + row0;
+        a_row_stride = p.a_ld;
+    } else {
+        abase = p.a_t + (int64_t)unit * p.k_pad * BM;
+        a_row_stride = BM;
+    }
+    uint32_t aoff_g[NIA];
+#pragma unroll
+    for (int i = 0; i < NIA; i++) {
+        int q = (i * 4 + w) * 64 + lane;           // linear 16-byte chunk of the tile
+        int row = q / CPA, pos = q - row * CPA;
+        int c16 = pos ^ swizzle_at<BM>(row);
+        if (p.dense && row0 + c16 * 8 >= p.N) c16 = 0;  // tokens beyond N: any valid data, the rows are not stored
+        aoff_g[i] = (uint32_t)((int64_t)row * a_row_stride * 2 + c16 * 16);
+    }
+    int wrow[NIW];
+    uint32_t wchunk[NIW];
+#pragma unroll
+    for (int i = 0; i < NIW; i++) {
+        wrow[i] = (i * 4 + w) * 4 + (lane >> 4);
+        wchunk[i] = (uint32_t)(((lane & 15) ^ swizzle_w2(wrow[i])) * 16);
+    }
+    const uint16_t* w2b = p.w2 + d0;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
+
+    int cols[NIW];
+    auto load_cols = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < NIW; i++) {
+            int pos = min(kt * kBK + wrow[i], count - 1);
+            cols[i] = idxp ? idxp[pos] : pos;
+        }
+    };
+    auto issue = [&](int kt, int stage) {
+        const uint16_t* as = abase + (int64_t)kt * kBK * a_row_stride;
+#pragma unroll
+        for (int i = 0; i < NIA; i++) load_global_to_lds_16B(as, aoff_g[i], lds0 + stage * STAGE + i * 4096);
+#pragma unroll
+        for (int i = 0; i < NIW; i++)
+            load_global_to_lds_16B(w2b, (uint32_t)cols[i] * (uint32_t)(p.D * 2) + wchunk[i],
+                                   lds0 + stage * STAGE + AT + i * 4096);
+    };
+
+    f32x16 acc[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
+
+    // Transposing reads.  For a k-step of 16 contraction rows, half h of the wave
+    // takes rows 8h..8h+7 as two groups of 4; inside a block of 16 lanes, lane i
+    // addresses row (i/4) of the group and 4 consecutive columns 4*(i%4).
+    const int trow = 8 * h + (l16 >> 2);           // + 4*rd, + 16*ks
+    const int tcol = 4 * (l16 & 3);                // element offset inside the 16-column block
+
+    if (ktiles > 0) {
+        load_cols(0);
+        issue(0, 0);
+        if (ktiles > 1) load_cols(1);
+    }
+    for (int kt = 0; kt < ktiles; kt++) {
+        const int stage = kt & 1;
+        wait_all_memory();
+        __syncthreads();
+        if (kt + 1 < ktiles) {
+            issue(kt + 1, stage ^ 1);
+            if (kt + 2 < ktiles) load_cols(kt + 2);
+        }
+        const uint8_t* sa = smem + stage * STAGE;
+        const uint8_t* sw = sa + AT;
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            bf16x8 bop[2];
+#pragma unroll
+            for (int nt = 0; nt < 2; nt++) {
+                short4v part[2];
+#pragma unroll
+                for (int rd = 0; rd < 2; rd++) {
+                    int row = ks * 16 + trow + 4 * rd;
+                    int col = wn * 64 + nt * 32 + mb * 16 + tcol;       // element column
+                    int c16 = (col >> 3) ^ swizzle_w2(row);
+                    part[rd] = lds_read_tr16(sw + row * 256 + c16 * 16 + (col & 7) * 2);
+                }
+                typedef __attribute__((ext_vector_type(8))) short short8v;
+                bop[nt] = __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                short4v part[2];
+#pragma unroll
+                for (int rd = 0; rd < 2; rd++) {
+                    int row = ks * 16 + trow + 4 * rd;
+                    int col = wm * (BM / 2) + mt * 32 + mb * 16 + tcol;  // token column
+                    int c16 = (col >> 3) ^ swizzle_at<BM>(row);
+                    part[rd] = lds_read_tr16(sa + row * RBA + c16 * 16 + (col & 7) * 2);
+                }
+                typedef __attribute__((ext_vector_type(8))) short short8v;
+                bf16x8 aop = __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                for (int nt = 0; nt < 2; nt++)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nt], acc[mt][nt], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- epilogue: fp32 tile through LDS, one half of the token rows at a time ----
+    const int l32 = lane & 31;
+    for (int half = 0; half < 2; half++) {
+        __syncthreads();
+        if (wm == half) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        int tl = mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                        int dl = wn * 64 + nt * 32 + l32;
+                        *reinterpret_cast<float*>(smem + tl * CS + dl * 4) = acc[mt][nt][r];
+                    }
+        }
+        __syncthreads();
+        for (int item = tid; item < (BM / 2) * 32; item += 256) {
+            int tl = item >> 5, ch = item & 31;
+            int tok = row0 + half * (BM / 2) + tl;
+            if (tok >= p.N) continue;
+            f32x4 a4 = *reinterpret_cast<const f32x4*>(smem + tl * CS + ch * 16);
+            uint16_t* orow = p.o + ((int64_t)b * p.N + tok) * p.D + d0 + ch * 4;
+            u32x2 old = u32x2{0, 0};
+            if (p.dense) {
+                if (p.bias) old = *reinterpret_cast<const u32x2*>(p.bias + d0 + ch * 4);
+            } else {
+                old = *reinterpret_cast<const u32x2*>(orow);
+            }
+            float o0 = bf16_bits_to_float(old[0] & 0xffffu) + a4[0];
+            float o1 = bf16_bits_to_float(old[0] >> 16) + a4[1];
+            float o2 = bf16_bits_to_float(old[1] & 0xffffu) + a4[2];
+            float o3 = bf16_bits_to_float(old[1] >> 16) + a4[3];
+            u32x2 res = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
+            *reinterpret_cast<u32x2*>(orow) = res;
+        }
+    }
+}
+
+// Chunk means of x in split precision: mean = hi + lo with hi = bf16(mean),
+// lo = bf16(mean - hi); out row = [hi(0..D-1) | lo(0..D-1)].  One thread per
+// (chunk, 8 consecutive columns); rows are read as 16-byte words.
+__global__ __launch_bounds__(256) void chunk_mean_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ xm,
+                                                         int N, int NB, int D, int c) {
+    const int unit = blockIdx.y;
+    const int b = unit / NB, chunk = unit % NB;
+    const int col8 = blockIdx.x * 256 + threadIdx.x;
+    if (col8 * 8 >= D) return;
+    const int r0 = chunk * c, r1 = min(N, r0 + c);
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r = r0; r < r1; r++) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(x + ((int64_t)b * N + r) * D + col8 * 8);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            s[2 * e] += bf16_bits_to_float(v[e] & 0xffffu);
+            s[2 * e + 1] += bf16_bits_to_float(v[e] >> 16);
+        }
+    }
+    const float inv = 1.f / (float)(r1 - r0);
+    u32x4 hi4, lo4;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        float m0 = s[2 * e] * inv, m1 = s[2 * e + 1] * inv;
+        uint32_t hp = pack_bf16x2(m0, m1);
+        hi4[e] = hp;
+        lo4[e] = pack_bf16x2(m0 - bf16_bits_to_float(hp & 0xffffu), m1 - bf16_bits_to_float(hp >> 16));
+    }
+    uint16_t* orow = xm + (int64_t)unit * 2 * D;
+    *reinterpret_cast<u32x4*>(orow + col8 * 8) = hi4;
+    *reinterpret_cast<u32x4*>(orow + D + col8 * 8) = lo4;
+}
+
+template <int BM, int MODE>
+static int32_t launch_gemm1(const Gemm1Params& p, int col_tiles, int units, hipStream_t s) {
+    constexpr int lds = 2 * (BM * 128 + kBN * 128);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)mlp_gemm1_kernel<BM, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds) != hipSuccess)
+            return CHIPMUNK_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((mlp_gemm1_kernel<BM, MODE>), dim3(col_tiles, units), dim3(256), lds, s, p);
+    return launch_status();
+}
+
+template <int BM>
+static int32_t launch_gemm2(const Gemm2Params& p, int col_tiles, int units, hipStream_t s) {
+    constexpr int stage = kBK * BM * 2 + kBK * 256;
+    constexpr int epi = (BM / 2) * (128 * 4 + 32);
+    constexpr int lds = 2 * stage > epi ? 2 * stage : epi;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)mlp_gemm2_kernel<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+            hipSuccess)
+            return CHIPMUNK_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3(col_tiles, units), dim3(256), lds, s, p);
+    return launch_status();
+}
+
+static int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+static int32_t check_mlp_shapes(int B, int N, int D, int F, int c) {
+    if (B < 1 || N < 1 || D < 1 || F < 1) return CHIPMUNK_ERR_SHAPE;
+    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (D % 128 != 0 || F % 64 != 0) return CHIPMUNK_ERR_UNSUPPORTED;
+    if ((int64_t)N * D * 2 >= (1LL << 32) || (int64_t)F * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    if ((int64_t)B * ((N + c - 1) / c) > 65535) return CHIPMUNK_ERR_SHAPE;
+    return CHIPMUNK_OK;
+}
+
+}  // namespace chipmunk
+
+using namespace chipmunk;
+
+extern "C" size_t chipmunk_mlp_workspace_bytes(int B, int N, int D, int F, int c, int k_stride) {
+    if (check_mlp_shapes(B, N, D, F, c) != CHIPMUNK_OK || k_stride < 0 || k_stride > F) return 0;
+    int64_t units = (int64_t)B * ((N + c - 1) / c);
+    return (size_t)(units * round_up(k_stride > 0 ? k_stride : 1, kBN) * c * 2);
+}
+
+extern "C" size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int c) {
+    if (B < 1 || N < 1 || D < 1 || (c != 128 && c != 192)) return 0;
+    int64_t units = (int64_t)B * ((N + c - 1) / c);
+    return (size_t)(round_up((int)units, 128) * 2 * (int64_t)D * 2);
+}
+
+extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                                             const uint16_t* w2, const int32_t* idx, const int32_t* counts,
+                                             uint16_t* a_cache, int64_t a_ld, uint16_t* o_cache, int B, int N,
+                                             int D, int F, int c, int k_stride, int act, void* ws,
+                                             size_t ws_bytes, void* stream) {
+    if (!x || !w1 || !w2 || !idx || !counts || !a_cache || !o_cache) return CHIPMUNK_ERR_NULL;
+    int32_t st = check_mlp_shapes(B, N, D, F, c);
+    if (st != CHIPMUNK_OK) return st;
+    if (k_stride < 0 || k_stride > F || a_ld < N) return CHIPMUNK_ERR_SHAPE;
+    if (act != CHIPMUNK_ACT_GELU_ERF && act != CHIPMUNK_ACT_GELU_TANH) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(a_cache) || !aligned16(o_cache) ||
+        !aligned16(idx) || !aligned16(counts) || !aligned16(ws) || (reinterpret_cast<uintptr_t>(b1) & 1u) ||
+        (a_ld % 8) != 0)
+        return CHIPMUNK_ERR_ALIGN;
+    if (k_stride == 0) return CHIPMUNK_OK;
+    size_t need = chipmunk_mlp_workspace_bytes(B, N, D, F, c, k_stride);
+    if (!ws || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
+    const int NB = (N + c - 1) / c, units = B * NB;
+    const int k_pad = round_up(k_stride, kBN);
+    hipStream_t s = (hipStream_t)stream;
+
+    Gemm1Params g1;
+    g1.x = x; g1.w1 = w1; g1.b1 = b1; g1.idx = idx; g1.counts = counts; g1.a_cache = a_cache;
+    g1.delta_t = (uint16_t*)ws; g1.out_f32 = nullptr; g1.a_ld = a_ld;
+    g1.N = N; g1.NB = NB; g1.D = D; g1.F = F; g1.K = D; g1.ldx = D;
+    g1.k_stride = k_stride; g1.k_pad = k_pad; g1.act = act;
+    st = c == 192 ? launch_gemm1<192, kSparseDelta>(g1, k_pad / kBN, units, s)
+                  : launch_gemm1<128, kSparseDelta>(g1, k_pad / kBN, units, s);
+    if (st != CHIPMUNK_OK) return st;
+
+    Gemm2Params g2;
+    g2.a_t = (const uint16_t*)ws; g2.w2 = w2; g2.bias = nullptr; g2.idx = idx; g2.counts = counts; g2.o = o_cache;
+    g2.a_ld = a_ld; g2.N = N; g2.NB = NB; g2.D = D; g2.F = F; g2.k_stride = k_stride; g2.k_pad = k_pad; g2.dense = 0;
+    return c == 192 ? launch_gemm2<192>(g2, D / kBN, units, s) : launch_gemm2<128>(g2, D / kBN, units, s);
+}
+
+extern "C" int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                                      const uint16_t* w2, const uint16_t* b2, uint16_t* out, uint16_t* a_cache,
+                                      int64_t a_ld, int B, int N, int D, int F, int c, int act, void* stream) {
+    if (!x || !w1 || !w2 || !out || !a_cache) return CHIPMUNK_ERR_NULL;
+    int32_t st = check_mlp_shapes(B, N, D, F, c);
+    if (st != CHIPMUNK_OK) return st;
+    if (a_ld < N) return CHIPMUNK_ERR_SHAPE;
+    if ((int64_t)F * a_ld * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    if (act != CHIPMUNK_ACT_GELU_ERF && act != CHIPMUNK_ACT_GELU_TANH) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(a_cache) || !aligned16(out) ||
+        (reinterpret_cast<uintptr_t>(b1) & 1u) || (reinterpret_cast<uintptr_t>(b2) & 7u) || (a_ld % 8) != 0)
+        return CHIPMUNK_ERR_ALIGN;
+    const int NB = (N + c - 1) / c, units = B * NB;
+    hipStream_t s = (hipStream_t)stream;
+
+    Gemm1Params g1;
+    g1.x = x; g1.w1 = w1; g1.b1 = b1; g1.idx = nullptr; g1.counts = nullptr; g1.a_cache = a_cache;
+    g1.delta_t = nullptr; g1.out_f32 = nullptr; g1.a_ld = a_ld;
+    g1.N = N; g1.NB = NB; g1.D = D; g1.F = F; g1.K = D; g1.ldx = D;
+    g1.k_stride = F; g1.k_pad = F; g1.act = act;
+    st = c == 192 ? launch_gemm1<192, kDenseAct>(g1, (F + kBN - 1) / kBN, units, s)
+                  : launch_gemm1<128, kDenseAct>(g1, (F + kBN - 1) / kBN, units, s);
+    if (st != CHIPMUNK_OK) return st;
+
+    Gemm2Params g2;
+    g2.a_t = a_cache; g2.w2 = w2; g2.bias = b2; g2.idx = nullptr; g2.counts = nullptr; g2.o = out;
+    g2.a_ld = a_ld; g2.N = N; g2.NB = NB; g2.D = D; g2.F = F; g2.k_stride = F; g2.k_pad = F; g2.dense = 1;
+    return c == 192 ? launch_gemm2<192>(g2, D / kBN, units, s) : launch_gemm2<128>(g2, D / kBN, units, s);
+}
+
+extern "C" int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16_t* w1, float* T, int B, int N,
+                                                 int D, int F, int c, void* ws, size_t ws_bytes, void* stream) {
+    if (!x || !w1 || !T) return CHIPMUNK_ERR_NULL;
+    int32_t st = check_mlp_shapes(B, N, D, F, c);
+    if (st != CHIPMUNK_OK) return st;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(T) || !aligned16(ws)) return CHIPMUNK_ERR_ALIGN;
+    size_t need = chipmunk_mlp_tile_mean_workspace_bytes(B, N, D, c);
+    if (!ws || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
+    const int NB = (N + c - 1) / c, units = B * NB;
+    if ((int64_t)round_up(units, 128) * 2 * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(chunk_mean_kernel, dim3((D / 8 + 255) / 256, units), dim3(256), 0, s, x, (uint16_t*)ws, N, NB, D, c);
+    if (launch_status() != CHIPMUNK_OK) return CHIPMUNK_ERR_LAUNCH;
+    // scores[unit, f] = <[hi | lo](unit), [w1_f | w1_f]>: a plain GEMM with "tokens" = units
+    Gemm1Params g1;
+    g1.x = (const uint16_t*)ws; g1.w1 = w1; g1.b1 = nullptr; g1.idx = nullptr; g1.counts = nullptr;
+    g1.a_cache = nullptr; g1.delta_t = nullptr; g1.out_f32 = T; g1.a_ld = 0;
+    g1.N = units; g1.NB = (units + 127) / 128; g1.D = D; g1.F = F; g1.K = 2 * D; g1.ldx = 2 * D;
+    g1.k_stride = F; g1.k_pad = F; g1.act = 0;
+    return launch_gemm1<128, kPlainF32>(g1, (F + kBN - 1) / kBN, g1.NB, s);
+}

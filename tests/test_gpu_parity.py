@@ -1,0 +1,375 @@
+"""GPU-vs-oracle parity, through the C ABI (via the thin Python binding).
+
+Bit-exact for permutations and selected indices; max relative error <= 2e-2
+(metric in tests/parity.py) for bf16 outputs computed with fp32 accumulation.
+Small cases are compared element by element over the whole tensor; at the full
+benchmark shapes the GPU runs the launch configuration bench.py times and
+sampled units (a unit = one (batch, head, chunk) or (batch, chunk), which the
+method treats independently) are compared one by one.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from parity import REL_TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def cm():
+    import paper_2506_03275_amd as cm
+    cm.load()
+    return cm
+
+
+def _u8(nbytes):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=DEV)
+
+
+# ------------------------------------------------------------------ reorder ---
+
+@pytest.mark.parametrize("geom", [
+    (0, 8, 8, 16, 0, 4, 4, 8),        # Tiny
+    (512, 1, 64, 64, 0, 1, 8, 8),     # FLUX-shaped
+    (0, 30, 48, 80, 256, 4, 6, 8),    # HunyuanVideo-shaped (T does not divide)
+    (0, 21, 45, 80, 0, 4, 6, 8),      # WAN-shaped (T, H do not divide)
+    (3, 5, 7, 9, 2, 2, 3, 4),         # nothing divides
+    (0, 1, 1, 1, 0, 1, 1, 1),         # one token
+])
+def test_voxel_reorder_bit_exact(cm, oracle, geom):
+    npre, T, H, W, nsuf, vt, vh, vw = geom
+    N = npre + T * H * W + nsuf
+    perm_ref, inv_ref = oracle.voxel_perm(*geom)
+    perm = torch.full((N,), -1, dtype=torch.int32, device=DEV)
+    inv = torch.full((N,), -1, dtype=torch.int32, device=DEV)
+    cm.voxel_reorder(None, None, perm, inv, npre, T, H, W, nsuf, vt, vh, vw)
+    assert np.array_equal(perm.cpu().numpy(), perm_ref)
+    assert np.array_equal(inv.cpu().numpy(), inv_ref)
+    # data: 16-byte rows path (bf16 x 24) and 4-byte path (int32 x 3), batch 2
+    g = si.generator(1, DEV)
+    for shape, dtype in (((2, N, 24), torch.bfloat16), ((2, N, 3), torch.int32)):
+        if dtype == torch.int32:
+            src = torch.randint(-2 ** 31, 2 ** 31 - 1, shape, generator=g, device=DEV, dtype=torch.int64).to(torch.int32)
+        else:
+            src = si.randn_bf16(shape, g)
+        dst = torch.empty_like(src)
+        cm.voxel_reorder(src, dst, None, None, npre, T, H, W, nsuf, vt, vh, vw, inverse=False)
+        raw = src.view(torch.uint8).cpu().numpy() if dtype == torch.int32 else src.view(torch.int16).cpu().numpy()
+        got = dst.view(torch.uint8).cpu().numpy() if dtype == torch.int32 else dst.view(torch.int16).cpu().numpy()
+        ref = oracle.reorder_rows(raw.reshape(2, N, -1), perm_ref, inverse=False)
+        assert np.array_equal(got.reshape(2, N, -1), ref)
+        back = torch.empty_like(src)
+        cm.voxel_reorder(dst, back, None, None, npre, T, H, W, nsuf, vt, vh, vw, inverse=True)
+        assert torch.equal(back, src)
+
+
+# -------------------------------------------------------------------- top-k ---
+
+@pytest.mark.parametrize("R,C,k,with_prev", [
+    (16, 1024, 256, False),      # Tiny attention
+    (8, 1024, 256, True),        # Tiny MLP
+    (5, 1000, 1000, False),      # k = C
+    (5, 1001, 1, True),          # k = 1, C % 4 != 0 (ld padded)
+    (3, 7, 3, False),
+    (24, 12288, 1229, True),     # FLUX MLP (row kept in LDS)
+    (6, 13824, 968, True),       # WAN MLP
+    (4, 14209, 100, False),      # just past the LDS limit: streaming path
+    (12, 4608, 323, False),      # FLUX attention
+    (3, 115456, 8082, False),    # HunyuanVideo attention row length
+    (3, 75600, 5292, True),
+])
+def test_topk_bit_exact(cm, oracle, R, C, k, with_prev):
+    g = si.generator(7, DEV)
+    ld = -(-C // 4) * 4
+    cur = torch.zeros((R, ld), dtype=torch.float32, device=DEV)
+    cur[:, :C] = torch.randn((R, C), generator=g, device=DEV)
+    prev = None
+    if with_prev:
+        prev = torch.zeros((R, ld), dtype=torch.float32, device=DEV)
+        prev[:, :C] = cur[:, :C] + 0.1 * torch.randn((R, C), generator=g, device=DEV)
+    idx = torch.full((R, k + 3), -7, dtype=torch.int32, device=DEV)
+    counts = torch.full((R,), -7, dtype=torch.int32, device=DEV)
+    cm.load().chipmunk_topk_cols(cur.data_ptr(), None if prev is None else prev.data_ptr(), R, C, ld, k,
+                                 idx.data_ptr(), counts.data_ptr(), k + 3, None)
+    torch.cuda.synchronize()
+    ref_idx, ref_counts = oracle.topk_cols(np.ascontiguousarray(cur[:, :C].cpu().numpy()),
+                                           None if prev is None else np.ascontiguousarray(prev[:, :C].cpu().numpy()),
+                                           k, k_stride=k + 3, idx_fill=-7)
+    assert np.array_equal(counts.cpu().numpy(), ref_counts)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+
+
+def test_topk_ties_and_structured_scores(cm, oracle):
+    """Heavy ties (quantised scores, zeros of both signs, constant rows) and the column-sum-like
+    distribution of the attention case: the tie rule (lower column wins) decides many picks."""
+    g = si.generator(11, DEV)
+    R, C = 6, 20000
+    cur = torch.round(torch.randn((R, C), generator=g, device=DEV) * 4) / 4      # ~30 distinct values
+    cur[1] = 0.0
+    cur[2, ::3] = -0.0
+    cur[3] = torch.softmax(torch.randn((C,), generator=g, device=DEV) * 3, dim=0) * 192
+    for k in (1, 17, 1400, C - 1):
+        idx = torch.zeros((R, k), dtype=torch.int32, device=DEV)
+        counts = torch.zeros((R,), dtype=torch.int32, device=DEV)
+        cm.topk_cols(cur, None, k, idx, counts)
+        ref_idx, _ = oracle.topk_cols(cur.cpu().numpy(), None, k)
+        assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    prev = torch.round(torch.randn((R, C), generator=g, device=DEV) * 4) / 4
+    idx = torch.zeros((R, 500), dtype=torch.int32, device=DEV)
+    counts = torch.zeros((R,), dtype=torch.int32, device=DEV)
+    cm.topk_cols(cur, prev, 500, idx, counts)
+    ref_idx, _ = oracle.topk_cols(cur.cpu().numpy(), prev.cpu().numpy(), 500)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+
+
+# ---------------------------------------------------------------- attention ---
+
+def _attn_case(B, H, N, E, c, k, seed, ragged):
+    (_, _, _), (q, kk, v), _ = si.attn_steps(B, H, N, E, seed, DEV)
+    NB = -(-N // c)
+    idx, counts = si.uniform_indices(B * H * NB, N, k, seed, DEV)
+    idx = idx.view(B, H, NB, k).contiguous()
+    counts = counts.view(B, H, NB).contiguous()
+    if ragged:
+        flat = counts.view(-1)
+        flat[0] = 0
+        flat[1 % flat.numel()] = 1
+        flat[-1] = max(1, k - 5)
+        if flat.numel() > 3:
+            flat[2] = min(k, 33)
+            flat[3] = min(k, 64)
+    base = si.randn_bf16((B, H, N, E), si.generator(seed + 9, DEV))
+    return q, kk, v, idx, counts, base
+
+
+@pytest.mark.parametrize("B,H,N,E,c,k,ragged", [
+    (1, 2, 1024, 64, 128, 256, False),     # Tiny (config 0)
+    (1, 2, 1000, 64, 128, 250, True),      # ragged last chunk, ragged counts
+    (1, 2, 1100, 128, 192, 100, True),
+    (2, 3, 700, 128, 128, 333, True),
+    (1, 1, 500, 64, 192, 77, True),
+    (1, 1, 192, 128, 192, 192, False),     # one chunk, every column
+    (1, 1, 50, 128, 192, 7, False),        # fewer rows than one MFMA tile group
+])
+def test_attn_sparse_delta_parity(cm, oracle, B, H, N, E, c, k, ragged):
+    q, kk, v, idx, counts, base = _attn_case(B, H, N, E, c, k, 0, ragged)
+    scale = 1.0 / math.sqrt(E)
+    qn, kn, vn = si.np_f32(q), si.np_f32(kk), si.np_f32(v)
+    basen = si.np_f32(base).astype(np.float64)
+    idxn, cntn = idx.cpu().numpy(), counts.cpu().numpy()
+    for o_scale in (1.0, -1.0):
+        out = torch.empty_like(base)
+        cm.attn_sparse_delta(q, kk, v, idx, counts, base, out, c, scale, o_scale)
+        ref = oracle.attn_sparse_delta(qn, kn, vn, idxn, cntn, basen, c, scale, o_scale)
+        assert rel_err(si.np_f32(out), ref) <= REL_TOL
+    # counts == 0 units return the cache bit for bit
+    NB = -(-N // c)
+    zero_units = np.argwhere(cntn == 0)
+    for b, h, i in zero_units:
+        assert torch.equal(out[b, h, i * c:(i + 1) * c], base[b, h, i * c:(i + 1) * c])
+    # in place: out aliases base
+    inplace = base.clone()
+    cm.attn_sparse_delta(q, kk, v, idx, counts, inplace, inplace, c, scale, -1.0)
+    assert torch.equal(inplace, out)
+
+
+def test_attn_all_columns_equals_dense_and_cache_roundtrip(cm, oracle):
+    """k = N reproduces dense attention; O_cache = O - Delta then O_cache + Delta returns O (Alg. 2)."""
+    B, H, N, E, c = 1, 2, 520, 128, 192
+    q, kk, v, idx, counts, _ = _attn_case(B, H, N, E, c, 60, 3, False)
+    scale = 1.0 / math.sqrt(E)
+    dense = torch.empty_like(q)
+    cm.attn_sparse_delta(q, kk, v, None, None, None, dense, c, scale, 1.0)
+    ref = oracle.attn_dense(si.np_f32(q), si.np_f32(kk), si.np_f32(v), c, scale)
+    assert rel_err(si.np_f32(dense), ref) <= REL_TOL
+    # each call is compared with the oracle applied to the call's own bf16 input cache
+    qn, kn, vn = si.np_f32(q), si.np_f32(kk), si.np_f32(v)
+    idxn, cntn = idx.cpu().numpy(), counts.cpu().numpy()
+    cache = torch.empty_like(q)
+    cm.attn_sparse_delta(q, kk, v, idx, counts, dense, cache, c, scale, -1.0)
+    cache_ref = oracle.attn_sparse_delta(qn, kn, vn, idxn, cntn, si.np_f32(dense).astype(np.float64), c, scale, -1.0)
+    assert rel_err(si.np_f32(cache), cache_ref) <= REL_TOL
+    again = torch.empty_like(q)
+    cm.attn_sparse_delta(q, kk, v, idx, counts, cache, again, c, scale, 1.0)
+    cache_n = si.np_f32(cache).astype(np.float64)
+    again_ref = oracle.attn_sparse_delta(qn, kn, vn, idxn, cntn, cache_n, c, scale, 1.0)
+    # Here the cache and the delta are each about three times larger than their sum (60 of 520 columns
+    # carry a softmax of their own), so the sum cancels: the delta itself is what the kernel computes
+    # and what the tolerance applies to.
+    assert rel_err(si.np_f32(again) - cache_n, again_ref - cache_n) <= REL_TOL
+    # the round trip returns the dense output up to the bf16 rounding of the stored cache, whose
+    # entries (dense minus delta) are larger than the dense output's: 2^-8 of the cache's largest entry
+    bound = float(np.abs(cache_ref).max()) * 2.0 ** -8 + REL_TOL * float(np.sqrt(np.mean(ref * ref)))
+    assert float(np.abs(si.np_f32(again) - ref).max()) <= bound
+
+
+@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (1, 2, 700, 128, 192)])
+def test_attn_dense_with_colsum_parity(cm, oracle, B, H, N, E, c):
+    (q, kk, v), _, _ = si.attn_steps(B, H, N, E, 5, DEV)
+    scale = 1.0 / math.sqrt(E)
+    NB = -(-N // c)
+    ld = -(-N // 4) * 4
+    out = torch.empty_like(q)
+    D = torch.full((B, H, NB, ld), -1.0, dtype=torch.float32, device=DEV)
+    ws = _u8(cm.attn_dense_workspace_bytes(B, H, N))
+    cm.attn_dense(q, kk, v, out, D, c, scale, ws)
+    ref, Dref = oracle.attn_dense(si.np_f32(q), si.np_f32(kk), si.np_f32(v), c, scale, want_colsum=True)
+    assert rel_err(si.np_f32(out), ref) <= REL_TOL
+    Dg = D.cpu().numpy()[..., :N].astype(np.float64)
+    assert rel_err(Dg, Dref) <= REL_TOL
+    rows = np.array([min(c, N - i * c) for i in range(NB)], np.float64)
+    assert np.allclose(Dg.sum(-1), rows[None, None], rtol=2e-3)     # each row of P sums to one
+
+
+def _check_sampled_attn_units(cm, oracle, name, n_units, sparse_k):
+    cfg = si.CONFIGS[name]
+    B, H, E, c = cfg["B"], cfg["H"], cfg["E"], cfg["c"]
+    N = si.config_tokens(cfg)
+    (_, _, _), (q, kk, v), _ = si.attn_steps(B, H, N, E, 0, DEV)
+    NB = -(-N // c)
+    idx, counts = si.uniform_indices(B * H * NB, N, sparse_k, 0, DEV)
+    idx = idx.view(B, H, NB, sparse_k)
+    counts = counts.view(B, H, NB)
+    base = si.randn_bf16((B, H, N, E), si.generator(9, DEV))
+    out = torch.empty_like(base)
+    scale = 1.0 / math.sqrt(E)
+    cm.attn_sparse_delta(q, kk, v, idx, counts, base, out, c, scale, 1.0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    units = [(0, 0, 0), (B - 1, H - 1, NB - 1)] + [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(NB)))
+                                                     for _ in range(n_units - 2)]
+    worst = 0.0
+    for b, h, i in units:
+        rows = slice(i * c, min(N, (i + 1) * c))
+        ref = oracle.attn_sparse_delta(si.np_f32(q[b:b + 1, h:h + 1, rows]), si.np_f32(kk[b:b + 1, h:h + 1]),
+                                       si.np_f32(v[b:b + 1, h:h + 1]),
+                                       np.ascontiguousarray(idx[b:b + 1, h:h + 1, i:i + 1].cpu().numpy()),
+                                       np.ascontiguousarray(counts[b:b + 1, h:h + 1, i:i + 1].cpu().numpy()),
+                                       si.np_f32(base[b:b + 1, h:h + 1, rows]).astype(np.float64), c, scale, 1.0)
+        worst = max(worst, rel_err(si.np_f32(out[b:b + 1, h:h + 1, rows]), ref))
+    assert worst <= REL_TOL
+
+
+def test_attn_flux_shape_sampled_units(cm, oracle):
+    _check_sampled_attn_units(cm, oracle, "flux", 12, 323)
+
+
+def test_attn_hunyuan_shape_sampled_units(cm, oracle):
+    _check_sampled_attn_units(cm, oracle, "hunyuan", 6, 8082)
+
+
+def test_attn_wan_shape_sampled_units(cm, oracle):
+    _check_sampled_attn_units(cm, oracle, "wan", 6, 5292)
+
+
+# ---------------------------------------------------------------------- MLP ---
+
+def _mlp_tensors(B, N, D, F, seed):
+    w1, b1, w2, b2 = si.mlp_weights(D, F, seed, DEV)
+    x1, x2 = si.mlp_steps(B, N, D, seed, DEV)
+    return x1, x2, w1, b1, w2, b2
+
+
+@pytest.mark.parametrize("B,N,D,F,c,act", [
+    (1, 1024, 256, 1024, 128, 1),          # Tiny (config 0)
+    (2, 500, 256, 320, 192, 0),            # ragged last chunk, erf GELU, F not a multiple of 128
+    (1, 200, 128, 64, 128, 1),
+])
+def test_mlp_dense_and_tile_mean_parity(cm, oracle, B, N, D, F, c, act):
+    x1, _, w1, b1, w2, b2 = _mlp_tensors(B, N, D, F, 0)
+    a_ld = -(-N // 8) * 8 + 8
+    out = torch.empty_like(x1)
+    a_cache = torch.zeros((B, F, a_ld), dtype=torch.bfloat16, device=DEV)
+    cm.mlp_dense(x1, w1, b1, w2, b2, out, a_cache, c, act)
+    ref, a_ref, T_ref = oracle.mlp_dense(si.np_f32(x1), si.np_f32(w1), si.np_f32(b1), si.np_f32(w2), si.np_f32(b2),
+                                         c, act, a_ld=a_ld)
+    assert rel_err(si.np_f32(a_cache)[..., :N], a_ref[..., :N]) <= REL_TOL
+    assert torch.all(a_cache[..., N:] == 0)                          # padding of the cache rows untouched
+    assert rel_err(si.np_f32(out), ref) <= REL_TOL
+    NB = -(-N // c)
+    T = torch.empty((B, NB, F), dtype=torch.float32, device=DEV)
+    ws = _u8(cm.mlp_tile_mean_workspace_bytes(B, N, D, c))
+    cm.mlp_tile_mean_preact(x1, w1, T, c, ws)
+    assert rel_err(T.cpu().numpy(), T_ref) <= 1e-3                   # split-precision mean: far tighter than bf16
+    assert rel_err(T.cpu().numpy(), oracle.mlp_tile_scores(si.np_f32(x1), si.np_f32(w1), c)) <= 1e-3
+
+
+@pytest.mark.parametrize("B,N,D,F,c,k,act", [
+    (1, 1024, 256, 1024, 128, 256, 1),     # Tiny (config 0)
+    (2, 500, 256, 320, 192, 100, 0),       # ragged chunk, counts not multiples of the tiles
+    (1, 300, 128, 256, 128, 256, 1),       # every neuron selected
+    (1, 192, 128, 128, 192, 1, 1),         # one neuron
+])
+def test_mlp_sparse_delta_parity(cm, oracle, B, N, D, F, c, k, act):
+    x1, x2, w1, b1, w2, b2 = _mlp_tensors(B, N, D, F, 1)
+    a_ld = -(-N // 8) * 8
+    NB = -(-N // c)
+    # caches of the dense step, from the oracle, rounded to the bf16 storage format
+    o_ref, a_ref, _ = oracle.mlp_dense(si.np_f32(x1), si.np_f32(w1), si.np_f32(b1), si.np_f32(w2), si.np_f32(b2),
+                                       c, act, a_ld=a_ld)
+    o_cache = torch.from_numpy(o_ref).to(torch.bfloat16).to(DEV)
+    a_cache = torch.from_numpy(a_ref).to(torch.bfloat16).to(DEV)
+    o_ref = si.np_f32(o_cache).astype(np.float64)
+    a_ref = si.np_f32(a_cache).astype(np.float64)
+    ws = _u8(cm.mlp_workspace_bytes(B, N, D, F, c, k))
+    for step in range(2):                                            # two sparse steps in a row on the same caches
+        idx, counts = si.uniform_indices(B * NB, F, k, 10 + step, DEV)
+        idx = idx.view(B, NB, k).contiguous()
+        counts = counts.view(B, NB).contiguous()
+        if k > 70:
+            counts[0, 0] = 0
+            counts[-1, -1] = 65
+            if NB > 1:
+                counts[0, 1] = k - 3
+        a_before = a_cache.clone()
+        cm.mlp_sparse_delta(x2, w1, b1, w2, idx, counts, a_cache, o_cache, c, act, ws)
+        oracle.mlp_sparse_delta(si.np_f32(x2), si.np_f32(w1), si.np_f32(b1), si.np_f32(w2), idx.cpu().numpy(),
+                                counts.cpu().numpy(), a_ref, o_ref, c, act)
+        assert rel_err(si.np_f32(a_cache)[..., :N], a_ref[..., :N]) <= REL_TOL
+        assert rel_err(si.np_f32(o_cache), o_ref) <= REL_TOL
+        # unselected cells of a_cache are untouched, bit for bit
+        touched = torch.zeros((B, F, a_ld), dtype=torch.bool, device=DEV)
+        for b in range(B):
+            for i in range(NB):
+                sel = idx[b, i, :int(counts[b, i])].long()
+                touched[b, sel, i * c:min(N, (i + 1) * c)] = True
+        assert torch.equal(a_cache[~touched], a_before[~touched])
+        x2 = si.perturb_all(x2, si.generator(77 + step, DEV))
+
+
+def test_mlp_flux_shape_sampled_units(cm, oracle):
+    cfg = si.CONFIGS["flux"]
+    B, D, F, c = cfg["B"], cfg["D"], cfg["F"], cfg["c"]
+    N = si.config_tokens(cfg)
+    k = si.kept(F, cfg["mlp_keep"])
+    x1, x2, w1, b1, w2, b2 = _mlp_tensors(B, N, D, F, 2)
+    NB = -(-N // c)
+    act = 1
+    out = torch.empty_like(x1)
+    a_cache = torch.zeros((B, F, N), dtype=torch.bfloat16, device=DEV)
+    cm.mlp_dense(x1, w1, b1, w2, b2, out, a_cache, c, act)
+    idx, counts = si.uniform_indices(B * NB, F, k, 3, DEV)
+    idx = idx.view(B, NB, k).contiguous()
+    counts = counts.view(B, NB).contiguous()
+    a0, o0 = a_cache.clone(), out.clone()
+    ws = _u8(cm.mlp_workspace_bytes(B, N, D, F, c, k))
+    cm.mlp_sparse_delta(x2, w1, b1, w2, idx, counts, a_cache, out, c, act, ws)
+    torch.cuda.synchronize()
+    w1n, b1n, w2n, b2n = si.np_f32(w1), si.np_f32(b1), si.np_f32(w2), si.np_f32(b2)
+    for i in (0, 7, NB - 1):                                          # sampled token chunks, each a B=1, N=c problem
+        rows = slice(i * c, min(N, (i + 1) * c))
+        n = rows.stop - rows.start
+        dref = oracle.mlp_dense(si.np_f32(x1[:, rows]), w1n, b1n, w2n, b2n, c, act, want_caches=False)
+        assert rel_err(si.np_f32(o0[:, rows]), dref) <= REL_TOL       # dense kernel at this shape
+        a_u = np.ascontiguousarray(si.np_f32(a0[:, :, rows]).astype(np.float64))
+        o_u = np.ascontiguousarray(si.np_f32(o0[:, rows]).astype(np.float64))
+        oracle.mlp_sparse_delta(si.np_f32(x2[:, rows]), w1n, b1n, w2n, np.ascontiguousarray(idx[:, i:i + 1].cpu().numpy()),
+                                np.ascontiguousarray(counts[:, i:i + 1].cpu().numpy()), a_u, o_u, c, act)
+        assert rel_err(si.np_f32(a_cache[:, :, rows]), a_u) <= REL_TOL
+        assert rel_err(si.np_f32(out[:, rows]), o_u) <= REL_TOL
