@@ -1,0 +1,328 @@
+#!/usr/bin/env python3
+"""Benchmark of the Chipmunk hot path on one MI355X.
+
+One "step" is one sparse-delta pass of a DiT block's attention + MLP over one
+batch of synthetic tokens, every stage on the GPU through the C ABI:
+  voxel reorder of the tokens -> top-k over the attention column sums ->
+  column-sparse delta attention -> token-merged MLP scores -> top-k over
+  |T - T_m| -> column-sparse delta MLP (GEMM1 + cache update, GEMM2 + merge).
+The caches the step reads (column sums D, O_cache, A_cache, M_cache, T_m) come
+from a dense step run once, untimed, with the library's dense kernels.
+
+The headline `value` is useful TFLOP/s: the FLOPs of the selected (chunk, key
+column) attention interactions and (chunk, hidden column) MLP interactions,
+4*E*rows*count per attention unit and 4*D*rows*count per MLP unit, divided by
+the whole step's time.  Softmax, GELU, index work and padding count as zero.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flux|hunyuan|wan|tiny]
+
+prints ONE JSON line.  Nothing here runs on more than one GPU.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+WORKLOAD_TEXT = {
+    "tiny": "Tiny: 1024 tokens (8x8x16 grid), 2 heads x 64, MLP 256->1024, chunk 128, keep 25%",
+    "flux": "FLUX.1-dev-shaped: 512 text + 4096 image tokens, 24 heads x 128, MLP 3072->12288, chunk 192, "
+            "keep 7% of key columns and 10% of hidden columns",
+    "hunyuan": "HunyuanVideo-shaped: 115200 video + 256 text tokens, 24 heads x 128, MLP 3072->12288, chunk 192, "
+               "93% column sparsity",
+    "wan": "WAN2.1-14B-shaped: 75600 video tokens, 40 heads x 128, MLP 5120->13824, chunk 192, 93% column sparsity",
+}
+
+
+class Timer:
+    """HIP event pairs on the current stream (the stream the binding launches on)."""
+
+    def __init__(self):
+        self.spans = {}
+
+    def span(self, name):
+        start = torch.cuda.Event(enable_timing=True)
+        stop = torch.cuda.Event(enable_timing=True)
+        self.spans.setdefault(name, []).append((start, stop))
+        return start, stop
+
+    def mean_ms(self, name):
+        spans = self.spans.get(name, [])
+        if not spans:
+            return None
+        return sum(a.elapsed_time(b) for a, b in spans) / len(spans)
+
+
+def build_state(cm, name, attn_keep, mlp_keep, seed, dev):
+    cfg = si.CONFIGS[name]
+    B, H, E, c, D, F = cfg["B"], cfg["H"], cfg["E"], cfg["c"], cfg["D"], cfg["F"]
+    N = si.config_tokens(cfg)
+    NB = -(-N // c)
+    attn_keep = cfg["attn_keep"] if attn_keep is None else attn_keep
+    mlp_keep = cfg["mlp_keep"] if mlp_keep is None else mlp_keep
+    k_a, k_m = si.kept(N, attn_keep), si.kept(F, mlp_keep)
+    st = dict(cfg=cfg, name=name, B=B, H=H, E=E, c=c, D=D, F=F, N=N, NB=NB, k_a=k_a, k_m=k_m,
+              scale=1.0 / math.sqrt(E), act=cm.ACT_GELU_TANH)
+    u8 = lambda n: torch.empty(max(int(n), 16), dtype=torch.uint8, device=dev)  # noqa: E731
+
+    # ---- dense step (untimed): fills every cache the sparse step reads -------------------------
+    (q1, k1, v1), (q2, k2, v2), _ = si.attn_steps(B, H, N, E, seed, dev)
+    ld = -(-N // 4) * 4
+    colsum = torch.empty((B, H, NB, ld), dtype=torch.float32, device=dev)
+    o_dense = torch.empty_like(q1)
+    cm.attn_dense(q1, k1, v1, o_dense, colsum, c, st["scale"], u8(cm.attn_dense_workspace_bytes(B, H, N)))
+    idx_a = torch.zeros((B, H, NB, max(k_a, 1)), dtype=torch.int32, device=dev)
+    cnt_a = torch.zeros((B, H, NB), dtype=torch.int32, device=dev)
+    cm.load().chipmunk_topk_cols(colsum.data_ptr(), None, B * H * NB, N, ld, k_a, idx_a.data_ptr(), cnt_a.data_ptr(),
+                                 idx_a.shape[-1], torch.cuda.current_stream().cuda_stream)
+    o_cache_attn = torch.empty_like(q1)
+    cm.attn_sparse_delta(q1, k1, v1, idx_a, cnt_a, o_dense, o_cache_attn, c, st["scale"], -1.0)
+    del q1, k1, v1, o_dense
+
+    w1, b1, w2, b2 = si.mlp_weights(D, F, seed, dev)
+    x1, x2 = si.mlp_steps(B, N, D, seed, dev)
+    a_cache = torch.zeros((B, F, -(-N // 8) * 8), dtype=torch.bfloat16, device=dev)
+    m_cache = torch.empty_like(x1)
+    cm.mlp_dense(x1, w1, b1, w2, b2, m_cache, a_cache, c, st["act"])
+    T_m = torch.empty((B, NB, F), dtype=torch.float32, device=dev)
+    ws_tm = u8(cm.mlp_tile_mean_workspace_bytes(B, N, D, c))
+    cm.mlp_tile_mean_preact(x1, w1, T_m, c, ws_tm)
+    del x1
+
+    # the step's token input arrives in raster order; the step's first stage reorders it
+    perm = torch.empty((N,), dtype=torch.int32, device=dev)
+    npre, (gt, gh, gw), nsuf, (vt, vh, vw) = cfg["n_prefix"], cfg["grid"], cfg["n_suffix"], cfg["voxel"]
+    cm.voxel_reorder(None, None, perm, None, npre, gt, gh, gw, nsuf, vt, vh, vw)
+    x_raster = torch.empty_like(x2)
+    cm.voxel_reorder(x2, x_raster, None, None, npre, gt, gh, gw, nsuf, vt, vh, vw, inverse=True)
+    torch.cuda.synchronize()
+
+    st.update(q=q2, k=k2, v=v2, colsum=colsum, ld=ld, idx_a=idx_a, cnt_a=cnt_a, o_cache_attn=o_cache_attn,
+              o_attn=torch.empty_like(q2), w1=w1, b1=b1, w2=w2, b2=b2, x_raster=x_raster, x=torch.empty_like(x2),
+              x_expect=x2, a_cache=a_cache, m_cache=m_cache, T_m=T_m, T=torch.empty_like(T_m), ws_tm=ws_tm,
+              idx_m=torch.zeros((B, NB, max(k_m, 1)), dtype=torch.int32, device=dev),
+              cnt_m=torch.zeros((B, NB), dtype=torch.int32, device=dev),
+              ws_mlp=u8(cm.mlp_workspace_bytes(B, N, D, F, c, max(k_m, 1))))
+    return st
+
+
+def sparse_step(cm, st, timer=None):
+    """One pass of the whole hot path.  With a timer, every stage is bracketed by events."""
+    cfg = st["cfg"]
+    npre, (gt, gh, gw), nsuf, (vt, vh, vw) = cfg["n_prefix"], cfg["grid"], cfg["n_suffix"], cfg["voxel"]
+    B, H, NB, N, F = st["B"], st["H"], st["NB"], st["N"], st["F"]
+    lib = cm.load()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def stage(name, fn):
+        if timer is None:
+            fn()
+            return
+        a, b = timer.span(name)
+        a.record()
+        fn()
+        b.record()
+
+    stage("voxel_reorder", lambda: cm.voxel_reorder(st["x_raster"], st["x"], None, None, npre, gt, gh, gw, nsuf,
+                                                    vt, vh, vw))
+    stage("topk_attn", lambda: lib.chipmunk_topk_cols(st["colsum"].data_ptr(), None, B * H * NB, N, st["ld"],
+                                                      st["k_a"], st["idx_a"].data_ptr(), st["cnt_a"].data_ptr(),
+                                                      st["idx_a"].shape[-1], stream))
+    stage("attn_sparse_delta", lambda: cm.attn_sparse_delta(st["q"], st["k"], st["v"], st["idx_a"], st["cnt_a"],
+                                                            st["o_cache_attn"], st["o_attn"], st["c"], st["scale"],
+                                                            1.0))
+    stage("mlp_tile_mean_preact", lambda: cm.mlp_tile_mean_preact(st["x"], st["w1"], st["T"], st["c"], st["ws_tm"]))
+    stage("topk_mlp", lambda: cm.topk_cols(st["T"].view(B * NB, F), st["T_m"].view(B * NB, F), st["k_m"],
+                                           st["idx_m"].view(B * NB, -1), st["cnt_m"].view(-1)))
+    stage("mlp_sparse_delta", lambda: cm.mlp_sparse_delta(st["x"], st["w1"], st["b1"], st["w2"], st["idx_m"],
+                                                          st["cnt_m"], st["a_cache"], st["m_cache"], st["c"],
+                                                          st["act"], st["ws_mlp"]))
+
+
+def dense_step(cm, st, timer):
+    out = st["o_attn"]
+    a, b = timer.span("attn_dense")
+    a.record()
+    cm.attn_sparse_delta(st["q"], st["k"], st["v"], None, None, None, out, st["c"], st["scale"], 1.0)
+    b.record()
+    a, b = timer.span("mlp_dense")
+    a.record()
+    cm.mlp_dense(st["x"], st["w1"], st["b1"], st["w2"], st["b2"], st["dense_out"], st["dense_a"], st["c"], st["act"])
+    b.record()
+
+
+def useful_flops(st):
+    rows_total = st["B"] * st["N"]
+    attn = 4.0 * st["E"] * st["H"] * rows_total * st["k_a"]
+    mlp = 4.0 * st["D"] * rows_total * st["k_m"]
+    return attn, mlp
+
+
+def cpu_baseline(st, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the same step's units, on the host cores."""
+    import oracle
+    oracle.build()
+    B, H, NB, N, E, c, D, F = (st[k] for k in ("B", "H", "NB", "N", "E", "c", "D", "F"))
+    rng = np.random.default_rng(0)
+    # attention units, each an independent (batch, head, chunk); cost 4*E*rows*k flops each
+    per_unit = 4.0 * E * c * max(st["k_a"], 1)
+    n_a = int(max(1, min(B * H * NB, (0.35 * budget_s * 4e9) // per_unit)))   # ~4 GFLOP/s assumed for sizing only
+    units = [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(NB))) for _ in range(n_a)]
+    heads = sorted({(b, h) for b, h, _ in units})
+    kv = {bh: (si.np_f32(st["k"][bh[0], bh[1]])[None, None], si.np_f32(st["v"][bh[0], bh[1]])[None, None])
+          for bh in heads[:8]}
+    units = [u for u in units if (u[0], u[1]) in kv]
+    prepared = []
+    for b, h, i in units:
+        rows = slice(i * c, min(N, (i + 1) * c))
+        prepared.append((si.np_f32(st["q"][b:b + 1, h:h + 1, rows]), kv[(b, h)][0], kv[(b, h)][1],
+                         np.ascontiguousarray(st["idx_a"][b:b + 1, h:h + 1, i:i + 1].cpu().numpy()),
+                         np.ascontiguousarray(st["cnt_a"][b:b + 1, h:h + 1, i:i + 1].cpu().numpy()),
+                         si.np_f32(st["o_cache_attn"][b:b + 1, h:h + 1, rows]).astype(np.float64),
+                         rows.stop - rows.start))
+    t0 = time.perf_counter()
+    fl_a = 0.0
+    for qn, kn, vn, idxn, cntn, basen, nrows in prepared:
+        oracle.attn_sparse_delta(qn, kn, vn, idxn, cntn, basen, c, st["scale"], 1.0)
+        fl_a += 4.0 * E * nrows * float(cntn.sum())
+    t_a = time.perf_counter() - t0
+    # MLP units, each an independent (batch, chunk)
+    per_unit = 4.0 * D * c * max(st["k_m"], 1)
+    n_m = int(max(1, min(B * NB, (0.65 * budget_s * 4e9) // per_unit)))
+    w1n, b1n, w2n = si.np_f32(st["w1"]), si.np_f32(st["b1"]), si.np_f32(st["w2"])
+    chunks = sorted({(int(rng.integers(B)), int(rng.integers(NB))) for _ in range(n_m)})
+    prepared = []
+    for b, i in chunks:
+        rows = slice(i * c, min(N, (i + 1) * c))
+        prepared.append((si.np_f32(st["x"][b:b + 1, rows]),
+                         np.ascontiguousarray(st["idx_m"][b:b + 1, i:i + 1].cpu().numpy()),
+                         np.ascontiguousarray(st["cnt_m"][b:b + 1, i:i + 1].cpu().numpy()),
+                         np.ascontiguousarray(si.np_f32(st["a_cache"][b:b + 1, :, rows]).astype(np.float64)),
+                         np.ascontiguousarray(si.np_f32(st["m_cache"][b:b + 1, rows]).astype(np.float64)),
+                         rows.stop - rows.start))
+    t0 = time.perf_counter()
+    fl_m = 0.0
+    for xn, idxn, cntn, an, on, nrows in prepared:
+        oracle.mlp_sparse_delta(xn, w1n, b1n, w2n, idxn, cntn, an, on, c, st["act"])
+        fl_m += 4.0 * D * nrows * float(cntn.sum())
+    t_m = time.perf_counter() - t0
+    total_s = t_a + t_m
+    return {
+        "value": (fl_a + fl_m) / total_s / 1e12 if total_s > 0 else None,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{len(units)} of {B * H * NB} attention units ({t_a:.1f} s) + {len(chunks)} of {B * NB} MLP chunks "
+                  f"({t_m:.1f} s) of this step, fp64 C oracle with OpenMP",
+        "attn_tflops": fl_a / t_a / 1e12 if t_a > 0 else None,
+        "mlp_tflops": fl_m / t_m / 1e12 if t_m > 0 else None,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="flux", choices=sorted(si.CONFIGS))
+    ap.add_argument("--attn-keep", type=float, default=None, help="fraction of key columns kept (default: the config's)")
+    ap.add_argument("--mlp-keep", type=float, default=None, help="fraction of hidden columns kept")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the hot path has no collectives; sharding is a design "
+              "note in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    big = args.workload in ("hunyuan", "wan")
+    steps = args.steps if args.steps is not None else (5 if big else 50)
+    warmup = args.warmup if args.warmup is not None else (1 if big else 5)
+
+    import paper_2506_03275_amd as cm
+    cm.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    st = build_state(cm, args.workload, args.attn_keep, args.mlp_keep, args.seed, dev)
+
+    for _ in range(warmup):
+        sparse_step(cm, st)
+    torch.cuda.synchronize()
+    timer = Timer()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        sparse_step(cm, st, timer)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    assert torch.equal(st["x"], st["x_expect"]), "voxel reorder did not restore the token order"
+
+    stages = {n: timer.mean_ms(n) for n in timer.spans}
+    fl_attn, fl_mlp = useful_flops(st)
+    value = (fl_attn + fl_mlp) / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the column-sparse attention kernel (one launch per step)
+    attn_ms = stages["attn_sparse_delta"]
+    achieved = fl_attn / (attn_ms * 1e-3) / 1e12
+    roofline = {"kernel": "attn_sparse_delta_kernel", "bound": "mfma", "achieved": achieved,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None, "launch_ms": attn_ms, "algorithmic_flops_per_launch": fl_attn}
+
+    extra = {"stage_ms": stages,
+             "attn_useful_tflops": achieved,
+             "mlp_useful_tflops": fl_mlp / (stages["mlp_sparse_delta"] * 1e-3) / 1e12}
+    if not args.no_dense:
+        st["dense_out"] = torch.empty_like(st["x"])
+        st["dense_a"] = torch.empty_like(st["a_cache"])
+        dt = Timer()
+        n_dense = 2 if big else 10
+        dense_step(cm, st, Timer())
+        for _ in range(n_dense):
+            dense_step(cm, st, dt)
+        torch.cuda.synchronize()
+        d_attn, d_mlp = dt.mean_ms("attn_dense"), dt.mean_ms("mlp_dense")
+        rows_total = st["B"] * st["N"]
+        extra["dense"] = {"attn_ms": d_attn, "mlp_ms": d_mlp,
+                          "attn_tflops": 4.0 * st["E"] * st["H"] * rows_total * st["N"] / (d_attn * 1e-3) / 1e12,
+                          "mlp_tflops": 4.0 * st["D"] * rows_total * st["F"] / (d_mlp * 1e-3) / 1e12}
+        extra["speedup_vs_dense"] = {
+            "attn_kernel": d_attn / attn_ms,
+            "mlp_kernels": d_mlp / stages["mlp_sparse_delta"],
+            "attn_plus_mlp_kernels": (d_attn + d_mlp) / (attn_ms + stages["mlp_sparse_delta"]),
+            "whole_step": (d_attn + d_mlp) / ms_per_step,
+        }
+        del st["dense_out"], st["dense_a"]
+
+    line = {
+        "metric": "sparse-delta attn+MLP useful TFLOP/s (whole step: reorder, top-k, scores, attention and MLP deltas)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "name": args.workload, "tokens": st["N"],
+                   "attn_columns_kept": st["k_a"], "mlp_columns_kept": st["k_m"],
+                   "attn_sparsity": 1.0 - st["k_a"] / st["N"], "mlp_sparsity": 1.0 - st["k_m"] / st["F"],
+                   "seed": args.seed},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(st)
+    line.update(extra)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
