@@ -2,10 +2,11 @@
 // Alg. 3), and dense attention as the special case "every column selected".
 //
 // One workgroup (4 waves) owns one chunk of c query rows of one (batch, head).
-// It walks the chunk's selected key columns in tiles of 64: the K and V rows
+// It walks the chunk's selected key columns in tiles of 32: the K and V rows
 // named by the index list are gathered from global memory straight into LDS
-// (16-byte asynchronous loads, one K or V row = E*2 contiguous bytes), double
-// buffered, and consumed by bf16 MFMA 16x16x32 with an fp32 online softmax.
+// (16-byte asynchronous loads, one K or V row = E*2 contiguous bytes) through
+// a ring of five tile buffers, so that three to four tiles are in flight while
+// one is consumed by bf16 MFMA 16x16x32 with an fp32 online softmax.
 //
 // Register-level layout.  Scores are produced transposed, S^T = K Q^T, so a
 // lane holds, for ONE query (lane % 16), the scores of 4 key rows per 16-row
@@ -33,7 +34,9 @@ struct AttnParams {
     float o_scale;
 };
 
-constexpr int kTileRows = 64;       // key rows per LDS tile
+constexpr int kTileRows = 32;         // key rows per LDS tile = one step of the online softmax
+constexpr int kStages = 5;            // ring of tile buffers (K tile + V tile each)
+constexpr int kColsumTileRows = 64;   // the column-sum kernel keeps 64-row tiles, double buffered
 constexpr float kRescaleSlack = 8.f;  // running max may lag the true max by 2^8 before a rescale
 
 // XOR swizzle of the 16-byte chunk position inside a row of the LDS tile,
@@ -48,14 +51,16 @@ __device__ __forceinline__ int swizzle(int row) {
 template <int E, int NQB>
 struct AttnState {
     f32x4 O[E / 16][NQB];
+    f32x4 L[NQB];     // softmax denominator, accumulated by the MFMA against a row of ones
     bf16x8 Q[E / 32][NQB];
     float m2[NQB];    // running reference max, in log2 units (score * sl2)
-    float lsum[NQB];  // this lane's share of the softmax denominator
 };
 
+// One tile of 32 selected key rows: S^T = K Q^T, online softmax, O^T += V^T P^T.
 template <int E, int NQB>
-__device__ __forceinline__ void attn_substep(AttnState<E, NQB>& st, const uint8_t* sK, const uint8_t* sV,
-                                             int koff, int voff, int kv0, int count, float sl2, int g) {
+__device__ __forceinline__ void attn_tile(AttnState<E, NQB>& st, const uint8_t* sK, const uint8_t* sV,
+                                          int koff, int voff, int kv0, int count, float sl2, int g,
+                                          bf16x8 ones) {
     constexpr int ROWB = E * 2;
     f32x4 S[2][NQB];
 #pragma unroll
@@ -73,7 +78,7 @@ __device__ __forceinline__ void attn_substep(AttnState<E, NQB>& st, const uint8_
                 S[u][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, st.Q[es][qb], S[u][qb], 0, 0, 0);
         }
     }
-    if (kv0 + 32 > count) {  // last, partly filled group of 32 rows: rows at or beyond count do not exist
+    if (kv0 + kTileRows > count) {  // last, partly filled tile: rows at or beyond count do not exist
 #pragma unroll
         for (int u = 0; u < 2; u++)
 #pragma unroll
@@ -100,7 +105,7 @@ __device__ __forceinline__ void attn_substep(AttnState<E, NQB>& st, const uint8_
             float mnew = fmaxf(st.m2[qb], mx[qb]);
             float alpha = __builtin_amdgcn_exp2f(st.m2[qb] - mnew);
             st.m2[qb] = mnew;
-            st.lsum[qb] *= alpha;
+            st.L[qb] *= alpha;
 #pragma unroll
             for (int eb = 0; eb < E / 16; eb++) st.O[eb][qb] *= alpha;
         }
@@ -112,14 +117,14 @@ __device__ __forceinline__ void attn_substep(AttnState<E, NQB>& st, const uint8_
 #pragma unroll
         for (int u = 0; u < 2; u++)
 #pragma unroll
-            for (int r = 0; r < 4; r++) {
+            for (int r = 0; r < 4; r++)
                 pv[u * 4 + r] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[u][qb][r], sl2, -st.m2[qb]));
-                st.lsum[qb] += pv[u * 4 + r];
-            }
         u32x4 packed;
 #pragma unroll
         for (int t = 0; t < 4; t++) packed[t] = pack_bf16x2(pv[2 * t], pv[2 * t + 1]);
         pop[qb] = __builtin_bit_cast(bf16x8, packed);
+        // denominator from the same bf16 probabilities that weight V
+        st.L[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pop[qb], st.L[qb], 0, 0, 0);
     }
 #pragma unroll
     for (int eb = 0; eb < E / 16; eb++) {
@@ -135,20 +140,27 @@ __device__ __forceinline__ void attn_substep(AttnState<E, NQB>& st, const uint8_
     }
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmem_at_most() {  // at most N vector-memory loads still in flight
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
 template <int E, int NQB>
 __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p) {
     constexpr int ROWB = E * 2;           // bytes per K/V row
     constexpr int CH = ROWB / 16;         // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // rows covered by one wave-wide 16-byte load
-    constexpr int NI = kTileRows / (RPI * 4);  // such loads per wave per tile
+    constexpr int NI = kTileRows / (RPI * 4);  // such loads per wave per tile and matrix
     constexpr int TILE = kTileRows * ROWB;
+    constexpr int STAGE = 2 * TILE;       // K tile then V tile
 
-    // two stages, each a K tile followed by a V tile
-    __shared__ __attribute__((aligned(1024))) uint8_t smem[4 * TILE];
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];  // kStages * STAGE bytes
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = tid >> 6;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
     const int g = lane >> 4;
     const int l16 = lane & 15;
 
@@ -158,7 +170,10 @@ __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p)
     const int row0 = chunk * p.c;
     const int rows_valid = min(p.c, p.N - row0);
     const int count = p.counts ? p.counts[unit] : p.N;
-    const int32_t* idxp = p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
+    // The index list is read-only for the whole launch: reading it through the constant
+    // address space lets uniform reads go through the scalar cache.
+    typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+    const_i32_ptr idxp = p.idx ? (const_i32_ptr)(uintptr_t)(p.idx + unit * (int64_t)p.k_stride) : nullptr;
 
     const int64_t head_off = bh * (int64_t)p.N * E;
     const uint16_t* qh = p.q + head_off;
@@ -180,7 +195,7 @@ __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p)
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
         st.m2[qb] = -INFINITY;
-        st.lsum[qb] = 0.f;
+        st.L[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int eb = 0; eb < E / 16; eb++) st.O[eb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
         int qrow = (w * NQB + qb) * 16 + l16;
@@ -193,67 +208,97 @@ __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p)
         }
     }
     const bool wave_active = w * NQB * 16 < rows_valid;
+    const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 
     // per-lane LDS read offsets (bytes) inside a 16-row group of a tile
     const int koff = l16 * ROWB + ((g ^ swizzle<E>(l16)) * 16);
     const int vrow = 4 * g + (l16 >> 2);
     const int voff = vrow * ROWB + (((((l16 & 3) >> 1)) ^ swizzle<E>(vrow)) * 16) + 8 * (l16 & 1);
 
-    // Gather bookkeeping.  Load i of this wave fills rows (i*4+w)*RPI + lane/CH of
-    // the tile; the lane owns LDS chunk position lane%CH of its row and therefore
-    // fetches the logical chunk  position ^ swizzle(row).
-    const int grow0 = w * RPI + lane / CH;  // row of load 0; load i adds 4*RPI*i
+    // Gather bookkeeping.  Load i of this wave fills rows (i*4+w)*RPI .. +RPI-1 of the
+    // tile; the lane owns row (i*4+w)*RPI + lane/CH, LDS chunk position lane%CH, and
+    // therefore fetches the logical chunk  position ^ swizzle(row).
+    const int sel = lane / CH;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
     const int ntiles = (count + kTileRows - 1) / kTileRows;
 
-    // Selected column per load, fetched one tile ahead and not touched until the
-    // gather that uses it (so the index fetch never stalls behind the transfers).
-    int cols[NI];
+    // The selected columns of a tile's rows are fetched through the scalar path (the
+    // rows of a load are wave-uniform), one tile ahead of the gather that uses them,
+    // so the vector-memory counter tracks the asynchronous tile transfers only.
+    // A wave fills 8 rows of a tile: row slot*4*RPI/... = wu*RPI + j for load 0 and
+    // (4+wu)*RPI + j for load 1 (E = 128: two loads of 4 rows; E = 64: one load of 8).
+    int c0 = 0, c1 = 0, c2 = 0, c3 = 0, c4 = 0, c5 = 0, c6 = 0, c7 = 0;
+    auto col_at = [&](int t, int row) -> int {
+        int pos = min(t * kTileRows + row, count - 1);
+        return idxp ? idxp[pos] : pos;
+    };
     auto load_cols = [&](int t) {
-#pragma unroll
-        for (int i = 0; i < NI; i++) {
-            int pos = min(t * kTileRows + grow0 + 4 * RPI * i, count - 1);
-            cols[i] = idxp ? idxp[pos] : pos;
-        }
+        const int r0 = wu * RPI;                       // first row of load 0
+        const int r1 = NI == 2 ? (4 + wu) * RPI : r0 + 4;  // first row of load 1, or rows 4..7 of load 0
+        c0 = col_at(t, r0); c1 = col_at(t, r0 + 1); c2 = col_at(t, r0 + 2); c3 = col_at(t, r0 + 3);
+        c4 = col_at(t, r1); c5 = col_at(t, r1 + 1); c6 = col_at(t, r1 + 2); c7 = col_at(t, r1 + 3);
     };
-    auto gather = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < NI; i++) {
-            int row = grow0 + 4 * RPI * i;
-            // byte offset of this lane's chunk inside the head's K (and V) matrix
-            uint32_t goff = (uint32_t)cols[i] * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
-            uint32_t dst = lds0 + (uint32_t)(stage * 2 * TILE + i * 4096);
-            load_global_to_lds_16B(kh, goff, dst);
-            load_global_to_lds_16B(vh, goff, dst + TILE);
+    auto issue = [&](int i, int col, int slot) {
+        int row = (i * 4 + w) * RPI + sel;
+        // byte offset of this lane's chunk inside the head's K (and V) matrix
+        uint32_t goff = (uint32_t)col * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
+        uint32_t dst = lds0 + (uint32_t)(slot * STAGE + i * 4096);
+        load_global_to_lds_16B(kh, goff, dst);
+        load_global_to_lds_16B(vh, goff, dst + TILE);
+    };
+    auto pick4 = [&](int a0, int a1, int a2, int a3, int which) -> int {
+        int lo = which & 1 ? a1 : a0, hi = which & 1 ? a3 : a2;
+        return which & 2 ? hi : lo;
+    };
+    auto gather = [&](int slot) {
+        if (NI == 2) {
+            issue(0, pick4(c0, c1, c2, c3, sel), slot);
+            issue(1, pick4(c4, c5, c6, c7, sel), slot);
+        } else {
+            int lo = pick4(c0, c1, c2, c3, sel & 3), hi = pick4(c4, c5, c6, c7, sel & 3);
+            issue(0, sel & 4 ? hi : lo, slot);
         }
     };
 
+    // The query loads must not be left pending into the loop: a wait for them inside
+    // the loop would also wait for every tile transfer in flight.
+    wait_all_memory();
+
+    // prologue: tiles 0 .. kStages-2 in flight
     load_cols(0);
-    gather(0);
-    if (ntiles > 1) load_cols(1);
+#pragma unroll 1
+    for (int s = 0; s < kStages - 1; s++) {
+        if (s < ntiles) gather(s);
+        load_cols(min(s + 1, ntiles - 1));
+    }
+    // c0..c7 now hold the columns of tile kStages-1
 
+    int slot = 0;
+#pragma unroll 1
     for (int t = 0; t < ntiles; t++) {
-        const int stage = t & 1;
-        wait_all_memory();
-        __syncthreads();  // tile t has landed in its stage; every wave is done with the other stage
-        if (t + 1 < ntiles) {
-            gather(stage ^ 1);
-            if (t + 2 < ntiles) load_cols(t + 2);
+        // tile t must have landed; tiles t+1 .. t+kStages-2 may stay in flight
+        if (t + kStages - 2 < ntiles)
+            wait_vmem_at_most<(kStages - 2) * 2 * NI>();
+        else
+            wait_all_memory();
+        __syncthreads();  // every wave sees tile t; every wave is done with tile t-1, whose slot is refilled now
+        int refill = slot == 0 ? kStages - 1 : slot - 1;
+        if (t + kStages - 1 < ntiles) {
+            gather(refill);
+            load_cols(min(t + kStages, ntiles - 1));
         }
         if (wave_active) {
-            const uint8_t* cK = smem + stage * 2 * TILE;
-            const uint8_t* cV = cK + TILE;
-            const int kv0 = t * kTileRows;
-            attn_substep<E, NQB>(st, cK, cV, koff, voff, kv0, count, p.sl2, g);
-            if (kv0 + 32 < count)
-                attn_substep<E, NQB>(st, cK + 32 * ROWB, cV + 32 * ROWB, koff, voff, kv0 + 32, count, p.sl2, g);
+            const uint8_t* cK = smem + slot * STAGE;
+            attn_tile<E, NQB>(st, cK, cK + TILE, koff, voff, t * kTileRows, count, p.sl2, g, ones);
         }
+        slot = slot == kStages - 1 ? 0 : slot + 1;
     }
 
     if (!wave_active) return;
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
-        float ltot = rows4_sum(st.lsum[qb]);
+        float ltot = st.L[qb][0];
         float f = p.o_scale / ltot;
         int qrow = (w * NQB + qb) * 16 + l16;
         if (qrow < rows_valid) {
@@ -298,10 +343,10 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
     constexpr int ROWB = E * 2;
     constexpr int CH = ROWB / 16;
     constexpr int RPI = 64 / CH;
-    constexpr int NI = kTileRows / (RPI * 4);
-    constexpr int TILE = kTileRows * ROWB;
+    constexpr int NI = kColsumTileRows / (RPI * 4);
+    constexpr int TILE = kColsumTileRows * ROWB;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * TILE];
-    __shared__ float s_part[2][4][kTileRows];
+    __shared__ float s_part[2][4][kColsumTileRows];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int g = lane >> 4, l16 = lane & 15;
@@ -337,20 +382,20 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
     const int koff = l16 * ROWB + ((g ^ swizzle<E>(l16)) * 16);
     const int grow0 = w * RPI + lane / CH;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
-    const int ntiles = (p.N + kTileRows - 1) / kTileRows;
+    const int ntiles = (p.N + kColsumTileRows - 1) / kColsumTileRows;
 
     auto gather = [&](int t, int stage) {
 #pragma unroll
         for (int i = 0; i < NI; i++) {
             int row = grow0 + 4 * RPI * i;
-            int pos = min(t * kTileRows + row, p.N - 1);
+            int pos = min(t * kColsumTileRows + row, p.N - 1);
             uint32_t goff = (uint32_t)pos * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
             load_global_to_lds_16B(kh, goff, lds0 + (uint32_t)(stage * TILE + i * 4096));
         }
     };
     auto flush = [&](int t) {  // sums of tile t: four waves' partials -> global
-        if (tid < kTileRows) {
-            int j = t * kTileRows + tid;
+        if (tid < kColsumTileRows) {
+            int j = t * kColsumTileRows + tid;
             float v = s_part[t & 1][0][tid] + s_part[t & 1][1][tid] + s_part[t & 1][2][tid] + s_part[t & 1][3][tid];
             if (j < p.N) drow[j] = v;
         }
@@ -397,17 +442,25 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
     flush(ntiles - 1);
 }
 
-static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_t s) {
-    dim3 grid((unsigned)units), block(256);
-    if (E == 128 && p.c == 192)
-        hipLaunchKernelGGL((attn_sparse_delta_kernel<128, 3>), grid, block, 0, s, p);
-    else if (E == 128 && p.c == 128)
-        hipLaunchKernelGGL((attn_sparse_delta_kernel<128, 2>), grid, block, 0, s, p);
-    else if (E == 64 && p.c == 192)
-        hipLaunchKernelGGL((attn_sparse_delta_kernel<64, 3>), grid, block, 0, s, p);
-    else
-        hipLaunchKernelGGL((attn_sparse_delta_kernel<64, 2>), grid, block, 0, s, p);
+template <int E, int NQB>
+static int32_t launch_attn_variant(const AttnParams& p, int64_t units, hipStream_t s) {
+    constexpr int lds = kStages * 2 * kTileRows * E * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return CHIPMUNK_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB>), dim3((unsigned)units), dim3(256), lds, s, p);
     return launch_status();
+}
+
+static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_t s) {
+    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3>(p, units, s);
+    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2>(p, units, s);
+    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3>(p, units, s);
+    return launch_attn_variant<64, 2>(p, units, s);
 }
 
 }  // namespace chipmunk
