@@ -35,16 +35,19 @@ struct AttnParams {
 };
 
 constexpr int kTileRows = 32;         // key rows per LDS tile = one step of the online softmax
-constexpr int kStages = 5;            // ring of tile buffers (K tile + V tile each)
+constexpr int kTilesPerStep = 2;      // tiles consumed between two workgroup barriers
+constexpr int kStages = 2 * kTilesPerStep;  // tile buffers (K tile + V tile each): one step in use, one in flight
 constexpr int kColsumTileRows = 64;   // the column-sum kernel keeps 64-row tiles, double buffered
 constexpr float kRescaleSlack = 8.f;  // running max may lag the true max by 2^8 before a rescale
 
-// XOR swizzle of the 16-byte chunk position inside a row of the LDS tile,
-// chosen so that both the 128-bit K reads (16 rows, one chunk) and the
-// transposing V reads (8 rows x 32 bytes) fall on distinct banks.
+// XOR swizzle of the 16-byte chunk position inside a row of the LDS tile.  For
+// 256-byte rows the map (a GF(2)-linear function of the row's low four bits) was
+// picked by measurement on gfx950 among all such maps: it is free of bank
+// conflicts both for the 128-bit K reads (16 rows, one chunk each per 16 lanes)
+// and for the transposing 64-bit V reads (4 rows x 32 bytes per 16 lanes).
 template <int E>
 __device__ __forceinline__ int swizzle(int row) {
-    if (E == 128) return ((row & 7) << 1) | ((row >> 3) & 1);
+    if (E == 128) return ((row & 1) << 1) ^ (((row >> 1) & 1) * 9) ^ (((row >> 2) & 1) << 2) ^ (((row >> 3) & 1) << 1);
     return (row >> 1) & 7;
 }
 
@@ -56,18 +59,20 @@ struct AttnState {
     float m2[NQB];    // running reference max, in log2 units (score * sl2)
 };
 
-// One tile of 32 selected key rows: S^T = K Q^T, online softmax, O^T += V^T P^T.
-template <int E, int NQB>
-__device__ __forceinline__ void attn_tile(AttnState<E, NQB>& st, const uint8_t* sK, const uint8_t* sV,
-                                          int koff, int voff, int kv0, int count, float sl2, int g,
-                                          bf16x8 ones) {
+// The work on one tile of 32 selected key rows is split in three pieces so that
+// the kernel can software-pipeline them: scores of tile t+1 (MFMA) are issued
+// next to the exponentials of tile t (VALU), and the max bookkeeping of tile t+1
+// (VALU) next to the P.V products of tile t (MFMA).
+
+// S^T = K Q^T for one tile; rows at or beyond `count` are set to -inf when MASK.
+template <int E, int NQB, bool MASK>
+__device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<E, NQB>& st, const uint8_t* sK,
+                                            int koff, int kv0, int count, int g) {
     constexpr int ROWB = E * 2;
-    f32x4 S[2][NQB];
 #pragma unroll
     for (int u = 0; u < 2; u++)
 #pragma unroll
         for (int qb = 0; qb < NQB; qb++) S[u][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
 #pragma unroll
     for (int es = 0; es < E / 32; es++) {
 #pragma unroll
@@ -78,7 +83,7 @@ __device__ __forceinline__ void attn_tile(AttnState<E, NQB>& st, const uint8_t* 
                 S[u][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, st.Q[es][qb], S[u][qb], 0, 0, 0);
         }
     }
-    if (kv0 + kTileRows > count) {  // last, partly filled tile: rows at or beyond count do not exist
+    if (MASK) {
 #pragma unroll
         for (int u = 0; u < 2; u++)
 #pragma unroll
@@ -89,7 +94,12 @@ __device__ __forceinline__ void attn_tile(AttnState<E, NQB>& st, const uint8_t* 
                     if (dead) S[u][qb][r] = -INFINITY;
             }
     }
-    // online softmax over the selected columns; the reference max is raised lazily
+}
+
+// Raise the reference max where this tile's scores exceed it by more than the
+// slack; O and the denominator are rescaled (rare after the first tiles).
+template <int E, int NQB>
+__device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB], float sl2) {
     float mx[NQB];
     bool need = false;
 #pragma unroll
@@ -110,6 +120,27 @@ __device__ __forceinline__ void attn_tile(AttnState<E, NQB>& st, const uint8_t* 
             for (int eb = 0; eb < E / 16; eb++) st.O[eb][qb] *= alpha;
         }
     }
+}
+
+// P = exp2(S*sl2 - m2) in bf16, the denominator, and O^T += V^T P^T.
+// The transposing V reads do not depend on the probabilities: the first kVPrefetch
+// operands are requested before the exponentials, the rest kVPrefetch steps ahead
+// of the MFMAs that consume them, so LDS latency stays off the MFMA chain.
+constexpr int kVPrefetch = 3;
+
+template <int E, int NQB>
+__device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB],
+                                                    const uint8_t* sV, int voff, float sl2, bf16x8 ones) {
+    constexpr int ROWB = E * 2;
+    constexpr int NEB = E / 16;
+    typedef __attribute__((ext_vector_type(8))) short short8v;
+    short4v vlo[NEB], vhi[NEB];
+#pragma unroll
+    for (int eb = 0; eb < kVPrefetch; eb++) {
+        vlo[eb] = lds_read_tr16(sV + (voff ^ (32 * eb)));
+        vhi[eb] = lds_read_tr16(sV + 16 * ROWB + (voff ^ (32 * eb)));
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kVPrefetch, 0);  // the LDS reads lead the block
     bf16x8 pop[NQB];
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
@@ -123,20 +154,25 @@ __device__ __forceinline__ void attn_tile(AttnState<E, NQB>& st, const uint8_t* 
 #pragma unroll
         for (int t = 0; t < 4; t++) packed[t] = pack_bf16x2(pv[2 * t], pv[2 * t + 1]);
         pop[qb] = __builtin_bit_cast(bf16x8, packed);
-        // denominator from the same bf16 probabilities that weight V
-        st.L[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pop[qb], st.L[qb], 0, 0, 0);
     }
+    // denominator from the same bf16 probabilities that weight V
 #pragma unroll
-    for (int eb = 0; eb < E / 16; eb++) {
-        int a = voff ^ (32 * eb);
-        short4v lo = lds_read_tr16(sV + a);
-        short4v hi = lds_read_tr16(sV + 16 * ROWB + a);
-        typedef __attribute__((ext_vector_type(8))) short short8v;
-        short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    for (int qb = 0; qb < NQB; qb++)
+        st.L[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pop[qb], st.L[qb], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, NQB, 0);
+#pragma unroll
+    for (int eb = 0; eb < NEB; eb++) {
+        if (eb + kVPrefetch < NEB) {
+            vlo[eb + kVPrefetch] = lds_read_tr16(sV + (voff ^ (32 * (eb + kVPrefetch))));
+            vhi[eb + kVPrefetch] = lds_read_tr16(sV + 16 * ROWB + (voff ^ (32 * (eb + kVPrefetch))));
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        short8v both = __builtin_shufflevector(vlo[eb], vhi[eb], 0, 1, 2, 3, 4, 5, 6, 7);
         bf16x8 vop = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
         for (int qb = 0; qb < NQB; qb++)
             st.O[eb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[qb], st.O[eb][qb], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NQB, 0);
     }
 }
 
@@ -146,12 +182,15 @@ __device__ __forceinline__ void wait_vmem_at_most() {  // at most N vector-memor
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int E, int NQB>
-__global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p) {
+// NWAVES waves per workgroup, each owning NQB blocks of 16 queries: c = 16 * NQB * NWAVES.
+template <int E, int NQB, int NWAVES>
+__global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_delta_kernel(AttnParams p) {
     constexpr int ROWB = E * 2;           // bytes per K/V row
     constexpr int CH = ROWB / 16;         // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // rows covered by one wave-wide 16-byte load
-    constexpr int NI = kTileRows / (RPI * 4);  // such loads per wave per tile and matrix
+    constexpr int NI = kTileRows / (RPI * NWAVES);  // such loads per wave per tile and matrix
+    constexpr int NC = NI * RPI;          // tile rows filled by one wave
+    constexpr int NT = 64 * NWAVES;
     constexpr int TILE = kTileRows * ROWB;
     constexpr int STAGE = 2 * TILE;       // K tile then V tile
 
@@ -169,7 +208,7 @@ __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p)
     const int chunk = (int)(unit % p.NB);
     const int row0 = chunk * p.c;
     const int rows_valid = min(p.c, p.N - row0);
-    const int count = p.counts ? p.counts[unit] : p.N;
+    const int count = __builtin_amdgcn_readfirstlane(p.counts ? p.counts[unit] : p.N);
     // The index list is read-only for the whole launch: reading it through the constant
     // address space lets uniform reads go through the scalar cache.
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
@@ -183,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p)
     uint16_t* outh = p.out + head_off;
 
     if (count <= 0) {  // nothing selected: the output is the cache, bit for bit
-        for (int t = tid; t < rows_valid * CH; t += 256) {
+        for (int t = tid; t < rows_valid * CH; t += NT) {
             int64_t off = (int64_t)(row0 + t / CH) * E + (t % CH) * 8;
             u32x4 val = baseh ? *reinterpret_cast<const u32x4*>(baseh + off) : u32x4{0, 0, 0, 0};
             *reinterpret_cast<u32x4*>(outh + off) = val;
@@ -216,83 +255,93 @@ __global__ __launch_bounds__(256, 2) void attn_sparse_delta_kernel(AttnParams p)
     const int vrow = 4 * g + (l16 >> 2);
     const int voff = vrow * ROWB + (((((l16 & 3) >> 1)) ^ swizzle<E>(vrow)) * 16) + 8 * (l16 & 1);
 
-    // Gather bookkeeping.  Load i of this wave fills rows (i*4+w)*RPI .. +RPI-1 of the
-    // tile; the lane owns row (i*4+w)*RPI + lane/CH, LDS chunk position lane%CH, and
-    // therefore fetches the logical chunk  position ^ swizzle(row).
+    // Gather bookkeeping.  Load i of this wave fills rows (i*NWAVES+w)*RPI .. +RPI-1 of
+    // the tile; the lane owns row (i*NWAVES+w)*RPI + lane/CH, LDS chunk position lane%CH,
+    // and therefore fetches the logical chunk  position ^ swizzle(row).
     const int sel = lane / CH;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
     const int ntiles = (count + kTileRows - 1) / kTileRows;
 
-    // The selected columns of a tile's rows are fetched through the scalar path (the
-    // rows of a load are wave-uniform), one tile ahead of the gather that uses them,
-    // so the vector-memory counter tracks the asynchronous tile transfers only.
-    // A wave fills 8 rows of a tile: row slot*4*RPI/... = wu*RPI + j for load 0 and
-    // (4+wu)*RPI + j for load 1 (E = 128: two loads of 4 rows; E = 64: one load of 8).
-    int c0 = 0, c1 = 0, c2 = 0, c3 = 0, c4 = 0, c5 = 0, c6 = 0, c7 = 0;
-    auto col_at = [&](int t, int row) -> int {
-        int pos = min(t * kTileRows + row, count - 1);
-        return idxp ? idxp[pos] : pos;
-    };
-    auto load_cols = [&](int t) {
-        const int r0 = wu * RPI;                       // first row of load 0
-        const int r1 = NI == 2 ? (4 + wu) * RPI : r0 + 4;  // first row of load 1, or rows 4..7 of load 0
-        c0 = col_at(t, r0); c1 = col_at(t, r0 + 1); c2 = col_at(t, r0 + 2); c3 = col_at(t, r0 + 3);
-        c4 = col_at(t, r1); c5 = col_at(t, r1 + 1); c6 = col_at(t, r1 + 2); c7 = col_at(t, r1 + 3);
-    };
-    auto issue = [&](int i, int col, int slot) {
-        int row = (i * 4 + w) * RPI + sel;
-        // byte offset of this lane's chunk inside the head's K (and V) matrix
-        uint32_t goff = (uint32_t)col * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
-        uint32_t dst = lds0 + (uint32_t)(slot * STAGE + i * 4096);
-        load_global_to_lds_16B(kh, goff, dst);
-        load_global_to_lds_16B(vh, goff, dst + TILE);
+    // The selected columns of the tile rows this wave fills are fetched through the
+    // scalar path (the rows of a load are wave-uniform), one step ahead of the gather
+    // that uses them, so the vector-memory counter tracks the asynchronous tile
+    // transfers only.  cols[s][i*RPI + j] belongs to row (i*NWAVES+w)*RPI + j of the
+    // s-th tile of a step.
+    int cols[kTilesPerStep][NC];
+#pragma unroll
+    for (int s = 0; s < kTilesPerStep; s++)
+#pragma unroll
+        for (int x = 0; x < NC; x++) cols[s][x] = 0;
+    auto load_cols = [&](int tile0) {  // columns of tiles tile0 .. tile0+kTilesPerStep-1
+        const int t0 = __builtin_amdgcn_readfirstlane(tile0);  // keeps the reads below on the scalar path
+        const int last = count - 1;
+#pragma unroll
+        for (int s = 0; s < kTilesPerStep; s++)
+#pragma unroll
+            for (int i = 0; i < NI; i++)
+#pragma unroll
+                for (int j = 0; j < RPI; j++) {
+                    int pos = min((t0 + s) * kTileRows + (i * NWAVES + wu) * RPI + j, last);
+                    cols[s][i * RPI + j] = idxp ? idxp[pos] : pos;
+                }
     };
     auto pick4 = [&](int a0, int a1, int a2, int a3, int which) -> int {
         int lo = which & 1 ? a1 : a0, hi = which & 1 ? a3 : a2;
         return which & 2 ? hi : lo;
     };
-    auto gather = [&](int slot) {
-        if (NI == 2) {
-            issue(0, pick4(c0, c1, c2, c3, sel), slot);
-            issue(1, pick4(c4, c5, c6, c7, sel), slot);
-        } else {
-            int lo = pick4(c0, c1, c2, c3, sel & 3), hi = pick4(c4, c5, c6, c7, sel & 3);
-            issue(0, sel & 4 ? hi : lo, slot);
-        }
+    auto gather = [&](int half) {  // fills buffers half*kTilesPerStep .. with the tiles whose columns are in cols
+#pragma unroll
+        for (int s = 0; s < kTilesPerStep; s++)
+#pragma unroll
+            for (int i = 0; i < NI; i++) {
+                int col = pick4(cols[s][i * RPI], cols[s][i * RPI + 1], cols[s][i * RPI + 2], cols[s][i * RPI + 3], sel & 3);
+                if (RPI == 8) {
+                    int hi = pick4(cols[s][i * RPI + 4], cols[s][i * RPI + 5], cols[s][i * RPI + 6], cols[s][i * RPI + 7], sel & 3);
+                    col = sel & 4 ? hi : col;
+                }
+                int row = (i * NWAVES + w) * RPI + sel;
+                // byte offset of this lane's chunk inside the head's K (and V) matrix
+                uint32_t goff = (uint32_t)col * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
+                uint32_t dst = lds0 + (uint32_t)((half * kTilesPerStep + s) * STAGE + i * NWAVES * 1024);
+                load_global_to_lds_16B(kh, goff, dst);
+                load_global_to_lds_16B(vh, goff, dst + TILE);
+            }
     };
 
     // The query loads must not be left pending into the loop: a wait for them inside
     // the loop would also wait for every tile transfer in flight.
     wait_all_memory();
 
-    // prologue: tiles 0 .. kStages-2 in flight
+    // first step in flight; columns of the second step requested
     load_cols(0);
-#pragma unroll 1
-    for (int s = 0; s < kStages - 1; s++) {
-        if (s < ntiles) gather(s);
-        load_cols(min(s + 1, ntiles - 1));
-    }
-    // c0..c7 now hold the columns of tile kStages-1
+    gather(0);
+    load_cols(kTilesPerStep);
 
-    int slot = 0;
+    int half = 0;  // which half of the buffers holds the step being consumed
 #pragma unroll 1
-    for (int t = 0; t < ntiles; t++) {
-        // tile t must have landed; tiles t+1 .. t+kStages-2 may stay in flight
-        if (t + kStages - 2 < ntiles)
-            wait_vmem_at_most<(kStages - 2) * 2 * NI>();
-        else
-            wait_all_memory();
-        __syncthreads();  // every wave sees tile t; every wave is done with tile t-1, whose slot is refilled now
-        int refill = slot == 0 ? kStages - 1 : slot - 1;
-        if (t + kStages - 1 < ntiles) {
-            gather(refill);
-            load_cols(min(t + kStages, ntiles - 1));
+    for (int t = 0; t < ntiles; t += kTilesPerStep) {
+        wait_all_memory();
+        __syncthreads();  // this step's tiles have landed for every wave; the other half is free to refill
+        if (t + kTilesPerStep < ntiles) {
+            gather(half ^ 1);
+            load_cols(t + 2 * kTilesPerStep);
         }
         if (wave_active) {
-            const uint8_t* cK = smem + slot * STAGE;
-            attn_tile<E, NQB>(st, cK, cK + TILE, koff, voff, t * kTileRows, count, p.sl2, g, ones);
+#pragma unroll
+            for (int s = 0; s < kTilesPerStep; s++) {
+                if (t + s < ntiles) {
+                    const uint8_t* cK = smem + (half * kTilesPerStep + s) * STAGE;
+                    f32x4 S[2][NQB];
+                    if (t + s + 1 < ntiles)
+                        attn_scores<E, NQB, false>(S, st, cK, koff, (t + s) * kTileRows, count, g);
+                    else
+                        attn_scores<E, NQB, true>(S, st, cK, koff, (t + s) * kTileRows, count, g);
+                    attn_update_max<E, NQB>(st, S, p.sl2);
+                    attn_weights_and_pv<E, NQB>(st, S, cK + TILE, voff, p.sl2, ones);
+                }
+            }
         }
-        slot = slot == kStages - 1 ? 0 : slot + 1;
+        half ^= 1;
     }
 
     if (!wave_active) return;
@@ -442,25 +491,25 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
     flush(ntiles - 1);
 }
 
-template <int E, int NQB>
+template <int E, int NQB, int NWAVES>
 static int32_t launch_attn_variant(const AttnParams& p, int64_t units, hipStream_t s) {
     constexpr int lds = kStages * 2 * kTileRows * E * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB>,
+        if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return CHIPMUNK_ERR_LAUNCH;
         attr_set = true;
     }
-    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB>), dim3((unsigned)units), dim3(256), lds, s, p);
+    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB, NWAVES>), dim3((unsigned)units), dim3(64 * NWAVES), lds, s, p);
     return launch_status();
 }
 
 static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_t s) {
-    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3>(p, units, s);
-    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2>(p, units, s);
-    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3>(p, units, s);
-    return launch_attn_variant<64, 2>(p, units, s);
+    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4>(p, units, s);
+    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4>(p, units, s);
+    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4>(p, units, s);
+    return launch_attn_variant<64, 2, 4>(p, units, s);
 }
 
 }  // namespace chipmunk

@@ -44,9 +44,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // serialise later LDS reads of OTHER buffers behind the outstanding transfer.
 __device__ __forceinline__ void load_global_to_lds_16B(const void* base, uint32_t byte_offset,
                                                        uint32_t lds_wave_base) {
+    // base and lds_wave_base are wave-uniform by contract; readfirstlane pins them to scalar registers
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32) |
+                        (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_wave_base), "v"(byte_offset), "s"(base)
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_wave_base)), "v"(byte_offset), "s"(ub)
                  : "memory");
 }
 
