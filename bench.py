@@ -97,7 +97,7 @@ def build_state(cm, name, attn_keep, mlp_keep, seed, dev):
     m_cache = torch.empty_like(x1)
     cm.mlp_dense(x1, w1, b1, w2, b2, m_cache, a_cache, c, st["act"])
     T_m = torch.empty((B, NB, F), dtype=torch.float32, device=dev)
-    ws_tm = u8(cm.mlp_tile_mean_workspace_bytes(B, N, D, c))
+    ws_tm = u8(cm.mlp_tile_mean_workspace_bytes(B, N, D, F, c))
     cm.mlp_tile_mean_preact(x1, w1, T_m, c, ws_tm)
     del x1
 

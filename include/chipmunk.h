@@ -107,7 +107,7 @@ int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, const uint16_t
                             void* ws, size_t ws_bytes, void* stream);
 
 /* Workspace bytes of chipmunk_mlp_tile_mean_preact (0 on bad arguments). */
-size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int c);
+size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int F, int c);
 
 /* Token-merged pre-activation (Alg. 7; T_m of Sec. 3.3.2):
  *   T[b,i,:] = (mean over the rows of chunk i of x[b]) @ w1^T, no bias.

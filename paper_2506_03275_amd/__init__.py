@@ -33,7 +33,7 @@ _SIGNATURES = {
     "chipmunk_attn_dense_workspace_bytes": ([_c_int] * 3, _c_size),
     "chipmunk_attn_dense": ([_c_ptr] * 5 + [_c_i64] + [_c_int] * 5 + [_c_f32, _c_ptr, _c_size, _c_ptr],
                             ctypes.c_int32),
-    "chipmunk_mlp_tile_mean_workspace_bytes": ([_c_int] * 4, _c_size),
+    "chipmunk_mlp_tile_mean_workspace_bytes": ([_c_int] * 5, _c_size),
     "chipmunk_mlp_tile_mean_preact": ([_c_ptr] * 3 + [_c_int] * 5 + [_c_ptr, _c_size, _c_ptr], ctypes.c_int32),
     "chipmunk_mlp_workspace_bytes": ([_c_int] * 6, _c_size),
     "chipmunk_mlp_sparse_delta": ([_c_ptr] * 7 + [_c_i64, _c_ptr] + [_c_int] * 7 + [_c_ptr, _c_size, _c_ptr],
@@ -145,8 +145,8 @@ def attn_dense(q, k, v, out, colsum, c, softmax_scale, ws=None):
                                       0 if ws is None else ws.numel(), _stream()), "chipmunk_attn_dense")
 
 
-def mlp_tile_mean_workspace_bytes(B, N, D, c):
-    return int(load().chipmunk_mlp_tile_mean_workspace_bytes(B, N, D, c))
+def mlp_tile_mean_workspace_bytes(B, N, D, F, c):
+    return int(load().chipmunk_mlp_tile_mean_workspace_bytes(B, N, D, F, c))
 
 
 def mlp_tile_mean_preact(x, w1, T, c, ws):

@@ -27,6 +27,22 @@ constexpr int kBK = 64;   // contraction tile
 
 enum Gemm1Mode { kSparseDelta = 0, kDenseAct = 1, kPlainF32 = 2 };
 
+// Workgroups are dispatched to the eight XCDs round-robin by linear id, and each
+// XCD has its own L2.  The tiles of one token chunk share that chunk's x rows
+// (GEMM1) or delta^T rows (GEMM2), so they are mapped to ids that are congruent
+// modulo 8: chunk u runs on XCD u % 8, its column tiles back to back.
+// Returns false for the padding ids of the last group of eight chunks.
+__device__ __forceinline__ bool xcd_tile_of_block(int col_tiles, int units, int* unit, int* col_tile) {
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int u = (slot / col_tiles) * 8 + xcd;
+    *unit = u;
+    *col_tile = slot % col_tiles;
+    return u < units;
+}
+static int xcd_grid_size(int col_tiles, int units) { return ((units + 7) / 8) * 8 * col_tiles; }
+
+
 __device__ __forceinline__ float gelu(float x, int act) {
     if (act == CHIPMUNK_ACT_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
     // tanh form: 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
@@ -46,6 +62,9 @@ struct Gemm1Params {
     int64_t a_ld;
     int N, NB, D, F, K, ldx; // K = contraction length (D, or 2D for the split-precision scores GEMM)
     int k_stride, k_pad, act;
+    int col_tiles, units;    // launch geometry (see xcd_tile_of_block)
+    int ksplit;              // kPlainF32 only: the contraction is cut in ksplit pieces, one workgroup each,
+                             // whose partial results go to out_f32 + piece * N * F (summed by a second kernel)
 };
 
 template <int BM, int MODE>
@@ -64,10 +83,17 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     const int wm = w >> 1, wn = w & 1;
     const int l32 = lane & 31, h = lane >> 5;
 
-    const int unit = blockIdx.y;                   // (batch, token chunk)
+    int unit, col_tile, piece = 0;                 // unit = (batch, token chunk)
+    if (MODE == kPlainF32) {  // few row blocks: plain order, spread over every XCD
+        col_tile = blockIdx.x % p.col_tiles;
+        unit = (blockIdx.x / p.col_tiles) % p.units;
+        piece = blockIdx.x / (p.col_tiles * p.units);
+    } else if (!xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile)) {
+        return;
+    }
     const int b = unit / p.NB, chunk = unit % p.NB;
     const int row0 = chunk * BM;
-    const int col0 = blockIdx.x * kBN;
+    const int col0 = col_tile * kBN;
     const int count = p.counts ? p.counts[unit] : p.F;
     if (col0 >= count && MODE != kSparseDelta) return;
     if (MODE == kSparseDelta && col0 >= ((count + kBK - 1) / kBK) * kBK) return;  // nothing to compute or to zero
@@ -122,13 +148,15 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     const int aoff = (wm * (BM / 2) + l32) * 128 + ((h ^ sw) * 16);
     const int boff = XT + (wn * 64 + l32) * 128 + ((h ^ sw) * 16);
 
-    const int ktiles = p.K / kBK;
-    issue(0, 0);
-    for (int kt = 0; kt < ktiles; kt++) {
-        const int stage = kt & 1;
+    const int ktiles_all = p.K / kBK;
+    const int kt_begin = MODE == kPlainF32 ? (int)((int64_t)ktiles_all * piece / p.ksplit) : 0;
+    const int kt_end = MODE == kPlainF32 ? (int)((int64_t)ktiles_all * (piece + 1) / p.ksplit) : ktiles_all;
+    issue(kt_begin, 0);
+    for (int kt = kt_begin; kt < kt_end; kt++) {
+        const int stage = (kt - kt_begin) & 1;
         wait_all_memory();
         __syncthreads();
-        if (kt + 1 < ktiles) issue(kt + 1, stage ^ 1);
+        if (kt + 1 < kt_end) issue(kt + 1, stage ^ 1);
         const uint8_t* sb = smem + stage * STAGE;
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
@@ -146,6 +174,8 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
         }
     }
 
+    wait_all_memory();  // an empty piece of a split contraction still has its first tile in flight
+
     if (MODE == kPlainF32) {
         // out[row, col] fp32; a lane holds one column and 4 consecutive rows per register group
 #pragma unroll
@@ -156,7 +186,8 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     int row = row0 + wm * (BM / 2) + mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                    if (row < p.N && col < p.F) p.out_f32[((int64_t)b * p.N + row) * p.F + col] = acc[mt][nt][r];
+                    if (row < p.N && col < p.F)
+                        p.out_f32[((int64_t)piece * p.N + row) * p.F + col] = acc[mt][nt][r];
                 }
             }
         return;
@@ -241,6 +272,7 @@ struct Gemm2Params {
     int64_t a_ld;
     int N, NB, D, F, k_stride, k_pad;
     int dense;
+    int col_tiles, units;    // launch geometry (see xcd_tile_of_block)
 };
 
 template <int BM>
@@ -267,10 +299,11 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
     const int wm = w >> 1, wn = w & 1;
     const int l16 = lane & 15, mb = (lane >> 4) & 1, h = lane >> 5;
 
-    const int unit = blockIdx.y;
+    int unit, col_tile;
+    if (!xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile)) return;
     const int b = unit / p.NB, chunk = unit % p.NB;
     const int row0 = chunk * BM;
-    const int d0 = blockIdx.x * kBN;
+    const int d0 = col_tile * kBN;
     const int count = p.counts ? p.counts[unit] : p.F;
     if (count <= 0 && !p.dense) return;            // nothing selected: the cache stays as it is
     const int32_t* idxp = p.idx ? p.idx + (int64_t)unit * p.k_stride : nullptr;
@@ -427,24 +460,37 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
 }
 
 // Chunk means of x in split precision: mean = hi + lo with hi = bf16(mean),
-// lo = bf16(mean - hi); out row = [hi(0..D-1) | lo(0..D-1)].  One thread per
-// (chunk, 8 consecutive columns); rows are read as 16-byte words.
+// lo = bf16(mean - hi); out row = [hi(0..D-1) | lo(0..D-1)].  A workgroup owns
+// (chunk, 512 columns): each wave sums a quarter of the chunk's rows for 64
+// groups of 8 columns (16-byte reads), the four partial sums meet in LDS.
 __global__ __launch_bounds__(256) void chunk_mean_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ xm,
                                                          int N, int NB, int D, int c) {
+    __shared__ float s_part[3][64][8];
     const int unit = blockIdx.y;
     const int b = unit / NB, chunk = unit % NB;
-    const int col8 = blockIdx.x * 256 + threadIdx.x;
-    if (col8 * 8 >= D) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int col8 = blockIdx.x * 64 + lane;
+    const bool live = col8 * 8 < D;
     const int r0 = chunk * c, r1 = min(N, r0 + c);
     float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int r = r0; r < r1; r++) {
-        u32x4 v = *reinterpret_cast<const u32x4*>(x + ((int64_t)b * N + r) * D + col8 * 8);
+    if (live) {
+        for (int r = r0 + w; r < r1; r += 4) {
+            u32x4 v = *reinterpret_cast<const u32x4*>(x + ((int64_t)b * N + r) * D + col8 * 8);
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            s[2 * e] += bf16_bits_to_float(v[e] & 0xffffu);
-            s[2 * e + 1] += bf16_bits_to_float(v[e] >> 16);
+            for (int e = 0; e < 4; e++) {
+                s[2 * e] += bf16_bits_to_float(v[e] & 0xffffu);
+                s[2 * e + 1] += bf16_bits_to_float(v[e] >> 16);
+            }
         }
     }
+    if (w > 0) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) s_part[w - 1][lane][e] = s[e];
+    }
+    __syncthreads();
+    if (w > 0 || !live) return;
+#pragma unroll
+    for (int e = 0; e < 8; e++) s[e] += s_part[0][lane][e] + s_part[1][lane][e] + s_part[2][lane][e];
     const float inv = 1.f / (float)(r1 - r0);
     u32x4 hi4, lo4;
 #pragma unroll
@@ -459,8 +505,20 @@ __global__ __launch_bounds__(256) void chunk_mean_kernel(const uint16_t* __restr
     *reinterpret_cast<u32x4*>(orow + D + col8 * 8) = lo4;
 }
 
+// out[i] = sum over the pieces of a split contraction, in piece order (deterministic)
+__global__ __launch_bounds__(256) void sum_pieces_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                         int64_t n4, int pieces) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    f32x4 acc = reinterpret_cast<const f32x4*>(part)[i];
+    for (int pc = 1; pc < pieces; pc++) acc += reinterpret_cast<const f32x4*>(part)[pc * n4 + i];
+    reinterpret_cast<f32x4*>(out)[i] = acc;
+}
+
 template <int BM, int MODE>
-static int32_t launch_gemm1(const Gemm1Params& p, int col_tiles, int units, hipStream_t s) {
+static int32_t launch_gemm1(Gemm1Params p, int col_tiles, int units, hipStream_t s) {
+    p.col_tiles = col_tiles;
+    p.units = units;
     constexpr int lds = 2 * (BM * 128 + kBN * 128);
     static bool attr_set = false;
     if (!attr_set) {
@@ -469,12 +527,15 @@ static int32_t launch_gemm1(const Gemm1Params& p, int col_tiles, int units, hipS
             return CHIPMUNK_ERR_LAUNCH;
         attr_set = true;
     }
-    hipLaunchKernelGGL((mlp_gemm1_kernel<BM, MODE>), dim3(col_tiles, units), dim3(256), lds, s, p);
+    const int grid = MODE == kPlainF32 ? col_tiles * units * p.ksplit : xcd_grid_size(col_tiles, units);
+    hipLaunchKernelGGL((mlp_gemm1_kernel<BM, MODE>), dim3(grid), dim3(256), lds, s, p);
     return launch_status();
 }
 
 template <int BM>
-static int32_t launch_gemm2(const Gemm2Params& p, int col_tiles, int units, hipStream_t s) {
+static int32_t launch_gemm2(Gemm2Params p, int col_tiles, int units, hipStream_t s) {
+    p.col_tiles = col_tiles;
+    p.units = units;
     constexpr int stage = kBK * BM * 2 + kBK * 256;
     constexpr int epi = (BM / 2) * (128 * 4 + 32);
     constexpr int lds = 2 * stage > epi ? 2 * stage : epi;
@@ -485,7 +546,7 @@ static int32_t launch_gemm2(const Gemm2Params& p, int col_tiles, int units, hipS
             return CHIPMUNK_ERR_LAUNCH;
         attr_set = true;
     }
-    hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3(col_tiles, units), dim3(256), lds, s, p);
+    hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3(xcd_grid_size(col_tiles, units)), dim3(256), lds, s, p);
     return launch_status();
 }
 
@@ -496,7 +557,7 @@ static int32_t check_mlp_shapes(int B, int N, int D, int F, int c) {
     if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
     if (D % 128 != 0 || F % 64 != 0) return CHIPMUNK_ERR_UNSUPPORTED;
     if ((int64_t)N * D * 2 >= (1LL << 32) || (int64_t)F * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
-    if ((int64_t)B * ((N + c - 1) / c) > 65535) return CHIPMUNK_ERR_SHAPE;
+    if ((int64_t)B * ((N + c - 1) / c) * ((F + kBN - 1) / kBN + D / kBN) > 0x3fffffffLL) return CHIPMUNK_ERR_SHAPE;
     return CHIPMUNK_OK;
 }
 
@@ -510,10 +571,23 @@ extern "C" size_t chipmunk_mlp_workspace_bytes(int B, int N, int D, int F, int c
     return (size_t)(units * round_up(k_stride > 0 ? k_stride : 1, kBN) * c * 2);
 }
 
-extern "C" size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int c) {
-    if (B < 1 || N < 1 || D < 1 || (c != 128 && c != 192)) return 0;
+// pieces the scores GEMM's contraction is cut into, so that a small problem still fills the GPU
+static int tile_mean_pieces(int units, int F) {
+    int blocks = ((units + 127) / 128) * ((F + kBN - 1) / kBN);
+    int pieces = 1;
+    while (pieces < 16 && blocks * pieces < 768) pieces *= 2;
+    return pieces;
+}
+
+extern "C" size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int F, int c) {
+    if (B < 1 || N < 1 || D < 1 || F < 1 || (c != 128 && c != 192)) return 0;
     int64_t units = (int64_t)B * ((N + c - 1) / c);
-    return (size_t)(round_up((int)units, 128) * 2 * (int64_t)D * 2);
+    if (units > 0x7fffff) return 0;
+    size_t means = (size_t)(units * 2 * (int64_t)D * 2);
+    means = (means + 255) / 256 * 256;
+    int pieces = tile_mean_pieces((int)units, F);
+    size_t partial = pieces > 1 ? (size_t)pieces * units * F * sizeof(float) : 0;
+    return means + partial;
 }
 
 extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
@@ -541,7 +615,7 @@ extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* 
     g1.x = x; g1.w1 = w1; g1.b1 = b1; g1.idx = idx; g1.counts = counts; g1.a_cache = a_cache;
     g1.delta_t = (uint16_t*)ws; g1.out_f32 = nullptr; g1.a_ld = a_ld;
     g1.N = N; g1.NB = NB; g1.D = D; g1.F = F; g1.K = D; g1.ldx = D;
-    g1.k_stride = k_stride; g1.k_pad = k_pad; g1.act = act;
+    g1.k_stride = k_stride; g1.k_pad = k_pad; g1.act = act; g1.ksplit = 1;
     st = c == 192 ? launch_gemm1<192, kSparseDelta>(g1, k_pad / kBN, units, s)
                   : launch_gemm1<128, kSparseDelta>(g1, k_pad / kBN, units, s);
     if (st != CHIPMUNK_OK) return st;
@@ -571,7 +645,7 @@ extern "C" int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, con
     g1.x = x; g1.w1 = w1; g1.b1 = b1; g1.idx = nullptr; g1.counts = nullptr; g1.a_cache = a_cache;
     g1.delta_t = nullptr; g1.out_f32 = nullptr; g1.a_ld = a_ld;
     g1.N = N; g1.NB = NB; g1.D = D; g1.F = F; g1.K = D; g1.ldx = D;
-    g1.k_stride = F; g1.k_pad = F; g1.act = act;
+    g1.k_stride = F; g1.k_pad = F; g1.act = act; g1.ksplit = 1;
     st = c == 192 ? launch_gemm1<192, kDenseAct>(g1, (F + kBN - 1) / kBN, units, s)
                   : launch_gemm1<128, kDenseAct>(g1, (F + kBN - 1) / kBN, units, s);
     if (st != CHIPMUNK_OK) return st;
@@ -588,18 +662,25 @@ extern "C" int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16
     int32_t st = check_mlp_shapes(B, N, D, F, c);
     if (st != CHIPMUNK_OK) return st;
     if (!aligned16(x) || !aligned16(w1) || !aligned16(T) || !aligned16(ws)) return CHIPMUNK_ERR_ALIGN;
-    size_t need = chipmunk_mlp_tile_mean_workspace_bytes(B, N, D, c);
-    if (!ws || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
+    size_t need = chipmunk_mlp_tile_mean_workspace_bytes(B, N, D, F, c);
+    if (!ws || need == 0 || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
     const int NB = (N + c - 1) / c, units = B * NB;
-    if ((int64_t)round_up(units, 128) * 2 * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    if ((int64_t)units * 2 * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(chunk_mean_kernel, dim3((D / 8 + 255) / 256, units), dim3(256), 0, s, x, (uint16_t*)ws, N, NB, D, c);
+    hipLaunchKernelGGL(chunk_mean_kernel, dim3((D / 8 + 63) / 64, units), dim3(256), 0, s, x, (uint16_t*)ws, N, NB, D, c);
     if (launch_status() != CHIPMUNK_OK) return CHIPMUNK_ERR_LAUNCH;
     // scores[unit, f] = <[hi | lo](unit), [w1_f | w1_f]>: a plain GEMM with "tokens" = units
+    const int pieces = tile_mean_pieces(units, F);
+    size_t means = ((size_t)units * 2 * D * 2 + 255) / 256 * 256;
+    float* partial = pieces > 1 ? (float*)((char*)ws + means) : T;
     Gemm1Params g1;
     g1.x = (const uint16_t*)ws; g1.w1 = w1; g1.b1 = nullptr; g1.idx = nullptr; g1.counts = nullptr;
-    g1.a_cache = nullptr; g1.delta_t = nullptr; g1.out_f32 = T; g1.a_ld = 0;
+    g1.a_cache = nullptr; g1.delta_t = nullptr; g1.out_f32 = partial; g1.a_ld = 0;
     g1.N = units; g1.NB = (units + 127) / 128; g1.D = D; g1.F = F; g1.K = 2 * D; g1.ldx = 2 * D;
-    g1.k_stride = F; g1.k_pad = F; g1.act = 0;
-    return launch_gemm1<128, kPlainF32>(g1, (F + kBN - 1) / kBN, g1.NB, s);
+    g1.k_stride = F; g1.k_pad = F; g1.act = 0; g1.ksplit = pieces;
+    st = launch_gemm1<128, kPlainF32>(g1, (F + kBN - 1) / kBN, g1.NB, s);
+    if (st != CHIPMUNK_OK || pieces == 1) return st;
+    int64_t n4 = (int64_t)units * F / 4;
+    hipLaunchKernelGGL(sum_pieces_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, partial, T, n4, pieces);
+    return launch_status();
 }

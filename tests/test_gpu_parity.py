@@ -294,7 +294,7 @@ def test_mlp_dense_and_tile_mean_parity(cm, oracle, B, N, D, F, c, act):
     assert rel_err(si.np_f32(out), ref) <= REL_TOL
     NB = -(-N // c)
     T = torch.empty((B, NB, F), dtype=torch.float32, device=DEV)
-    ws = _u8(cm.mlp_tile_mean_workspace_bytes(B, N, D, c))
+    ws = _u8(cm.mlp_tile_mean_workspace_bytes(B, N, D, F, c))
     cm.mlp_tile_mean_preact(x1, w1, T, c, ws)
     assert rel_err(T.cpu().numpy(), T_ref) <= 1e-3                   # split-precision mean: far tighter than bf16
     assert rel_err(T.cpu().numpy(), oracle.mlp_tile_scores(si.np_f32(x1), si.np_f32(w1), c)) <= 1e-3
