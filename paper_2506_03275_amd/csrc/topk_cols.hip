@@ -1,26 +1,46 @@
 // Exact per-row top-k column selection (Sec. 3.3.1 idx = TopK_k(D); Alg. 7
 // idx = TopK(|T - T_m|)) for gfx950.
 //
-// One workgroup per row.  Scores are mapped to order-preserving 32-bit keys;
-// the k-th largest key is found by a most-significant-digit radix select
-// (11 + 11 + 10 bits, LDS histograms, wave-level prefix sums on DPP), then one
-// ordered pass emits every column above the threshold plus the first columns
-// equal to it, in ascending column order.  Rows of up to kLdsCols columns are
-// read from HBM once and kept in LDS as keys; longer rows are re-read (they
-// stay in L2 / Infinity Cache between the passes).
+// One workgroup per row.  Scores are mapped to order-preserving 32-bit keys.
+// The k-th largest key (the threshold) is found by a most-significant-digit
+// radix select (digits of up to 11 bits, LDS histograms, wave-level prefix
+// sums on DPP); the selected columns are every column above the threshold plus
+// the first columns equal to it, written in ascending column order.
+//   - Rows of up to kLdsCols columns are read from HBM once and kept in LDS as
+//     keys; every pass runs on LDS.
+//   - Longer rows (the attention column sums, 10^5 columns) are read from HBM
+//     once as well: two pivots taken from a 4096-score sample bracket the
+//     threshold; the single pass over the row marks the columns above the
+//     upper pivot in a bit mask in LDS and collects the few thousand scores
+//     between the pivots; the exact threshold is selected among those, their
+//     bits are added, and the indices are written from the mask.  If the
+//     bracket misses (probability about 1e-3 per row), if the candidates
+//     overflow (heavy ties) or if the mask would not fit LDS, the row falls
+//     back to histogram passes over global memory: the result is exact in
+//     every case.
 #include "common.h"
+
+#include <algorithm>
 
 namespace chipmunk {
 
-constexpr int kLdsCols = 14208;  // 55.5 KB of keys + 8 KB histogram fit one 64 KB LDS allocation
+constexpr int kLdsCols = 14208;   // 55.5 KB of keys + 8 KB histogram fit one 64 KB LDS allocation
 constexpr int kBins = 2048;
+constexpr float kPivotSigmas = 3.5f;  // slack of the sample pivots around the threshold, in standard deviations
 
-__device__ __forceinline__ uint32_t score_key(float cur, const float* prev_ptr) {
-    float s = cur;
-    if (prev_ptr) s = fabsf(cur - *prev_ptr);
+// key(a) > key(b) exactly when a > b; no finite or infinite score has key 0
+__device__ __forceinline__ uint32_t key_of_score(float s) {
     if (s == 0.f) s = 0.f;  // -0 and +0 are the same score
     uint32_t u = __float_as_uint(s);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float score_of_key(uint32_t key) {
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+__device__ __forceinline__ uint32_t score_key(float cur, float prev, bool has_prev) {
+    return key_of_score(has_prev ? fabsf(cur - prev) : cur);
 }
 
 // inclusive prefix sum over the 64 lanes of a wave: DPP row shifts inside each
@@ -52,145 +72,598 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
     return before + inc - v;
 }
 
-template <bool LDS_ROW>
-__global__ __launch_bounds__(256) void topk_cols_kernel(const float* __restrict__ cur,
-                                                        const float* __restrict__ prev, int C, int64_t ld,
-                                                        int k, int32_t* __restrict__ idx,
-                                                        int32_t* __restrict__ counts, int k_stride) {
-    __shared__ uint32_t s_hist[kBins];
-    __shared__ uint32_t s_keys[LDS_ROW ? kLdsCols : 4];
-    __shared__ uint32_t s_wave[4];
-    __shared__ uint32_t s_pick[2];
+// Key sources hand out four consecutive keys per call in two steps, so that a caller
+// can issue several loads before it consumes the first: load(j4) fetches group j4
+// (clamped to the last group, hence always in bounds and free of branches), keys()
+// turns what was loaded into keys and returns how many of the four exist (0 when j4
+// lies past the end).
 
-    const int tid = threadIdx.x;
-    const int64_t row = blockIdx.x;
-    const float* crow = cur + row * ld;
-    const float* prow = prev ? prev + row * ld : nullptr;
-    int32_t* out = idx + row * (int64_t)k_stride;
-    if (tid == 0) counts[row] = k;
-    if (k == 0) return;
-
-    const int C4 = (C + 3) >> 2;  // rows are read as 4-column groups (ld % 4 == 0 keeps them aligned)
-
-    // keys of columns 4*j4 .. 4*j4+3; columns at or beyond C do not exist (valid = how many do)
-    auto keys4 = [&](int j4, uint32_t (&key)[4]) -> int {
-        int valid = min(4, C - 4 * j4);
-        if (LDS_ROW) {
-            uint4 kk = *reinterpret_cast<const uint4*>(&s_keys[4 * j4]);
-            key[0] = kk.x; key[1] = kk.y; key[2] = kk.z; key[3] = kk.w;
-        } else {
-            float4 c4 = *reinterpret_cast<const float4*>(crow + 4 * j4);
-            float cv[4] = {c4.x, c4.y, c4.z, c4.w};
-            float pv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (prow) {
-                float4 p4 = *reinterpret_cast<const float4*>(prow + 4 * j4);
-                pv[0] = p4.x; pv[1] = p4.y; pv[2] = p4.z; pv[3] = p4.w;
-            }
-#pragma unroll
-            for (int e = 0; e < 4; e++) key[e] = score_key(cv[e], prow ? &pv[e] : nullptr);
-        }
-        return valid;
+// A row in global memory.
+template <bool HAS_PREV>
+struct GlobalRowKeys {
+    const float* cur;
+    const float* prev;
+    int C;
+    struct Raw {
+        float4 c, p;
     };
-
-    if (LDS_ROW) {
-        for (int j4 = tid; j4 < C4; j4 += 256) {
-            float4 c4 = *reinterpret_cast<const float4*>(crow + 4 * j4);
-            float cv[4] = {c4.x, c4.y, c4.z, c4.w};
-            float pv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (prow) {
-                float4 p4 = *reinterpret_cast<const float4*>(prow + 4 * j4);
-                pv[0] = p4.x; pv[1] = p4.y; pv[2] = p4.z; pv[3] = p4.w;
-            }
-            uint4 kk;
-            kk.x = score_key(cv[0], prow ? &pv[0] : nullptr);
-            kk.y = score_key(cv[1], prow ? &pv[1] : nullptr);
-            kk.z = score_key(cv[2], prow ? &pv[2] : nullptr);
-            kk.w = score_key(cv[3], prow ? &pv[3] : nullptr);
-            *reinterpret_cast<uint4*>(&s_keys[4 * j4]) = kk;
-        }
+    __device__ __forceinline__ Raw load(int j4) const {
+        const int j = min(j4, ((C + 3) >> 2) - 1);
+        Raw r;
+        r.c = *reinterpret_cast<const float4*>(cur + 4 * j);
+        if constexpr (HAS_PREV)
+            r.p = *reinterpret_cast<const float4*>(prev + 4 * j);
+        else
+            r.p = float4{0.f, 0.f, 0.f, 0.f};
+        return r;
     }
+    __device__ __forceinline__ int keys(const Raw& r, int j4, uint32_t (&key)[4]) const {
+        key[0] = score_key(r.c.x, r.p.x, HAS_PREV);
+        key[1] = score_key(r.c.y, r.p.y, HAS_PREV);
+        key[2] = score_key(r.c.z, r.p.z, HAS_PREV);
+        key[3] = score_key(r.c.w, r.p.w, HAS_PREV);
+        return max(0, min(4, C - 4 * j4));
+    }
+};
 
-    // ---- radix select of the k-th largest key -------------------------------
-    uint32_t known = 0;       // the digits fixed so far, in place
-    uint32_t want = (uint32_t)k;  // rank still to be found among the keys that match `known`
-    const int shifts[3] = {21, 10, 0};
-    const int widths[3] = {11, 11, 10};
-#pragma unroll 1
-    for (int pass = 0; pass < 3; pass++) {
-        const int shift = shifts[pass];
-        const uint32_t digit_mask = (1u << widths[pass]) - 1u;
-        const uint32_t hi_mask = pass == 0 ? 0u : ~((1u << (shift + widths[pass])) - 1u);
-        for (int b = tid; b < kBins; b += 256) s_hist[b] = 0;
-        __syncthreads();
-        for (int j4 = tid; j4 < C4; j4 += 256) {
-            uint32_t key[4];
-            int valid = keys4(j4, key);
+// Keys already in LDS (a whole short row, a sample, or the candidates of a long row).
+struct LdsKeys {
+    const uint32_t* data;
+    int n;
+    typedef uint4 Raw;
+    __device__ __forceinline__ Raw load(int j4) const {
+        return *reinterpret_cast<const uint4*>(data + 4 * min(j4, ((n + 3) >> 2) - 1));
+    }
+    __device__ __forceinline__ int keys(const Raw& r, int j4, uint32_t (&key)[4]) const {
+        key[0] = r.x; key[1] = r.y; key[2] = r.z; key[3] = r.w;
+        return max(0, min(4, n - 4 * j4));
+    }
+};
+
+// One radix digit: s_hist[d] = how many of the n keys behind `src` agree with `known`
+// on the bits selected by hi_mask and have digit d = (key >> shift) & digit_mask.
+template <typename Src>
+__device__ __forceinline__ void digit_histogram(const Src& src, int n, uint32_t known, uint32_t hi_mask, int shift,
+                                                uint32_t digit_mask, uint32_t* s_hist) {
+    const int tid = threadIdx.x;
+    const int n4 = (n + 3) >> 2;
+    __syncthreads();
+    for (int b = tid; b < kBins; b += 256) s_hist[b] = 0;
+    __syncthreads();
+    for (int j4 = tid; j4 < n4; j4 += 512) {
+        typename Src::Raw raw0 = src.load(j4), raw1 = src.load(j4 + 256);
+        uint32_t key[2][4];
+        int valid[2];
+        valid[0] = src.keys(raw0, j4, key[0]);
+        valid[1] = src.keys(raw1, j4 + 256, key[1]);
+#pragma unroll
+        for (int h = 0; h < 2; h++)
 #pragma unroll
             for (int e = 0; e < 4; e++)
-                if (e < valid && (key[e] & hi_mask) == known) atomicAdd(&s_hist[(key[e] >> shift) & digit_mask], 1u);
-        }
-        __syncthreads();
-        // thread t owns the 8 bins 2047-8t .. 2040-8t (descending); find where the
-        // count from the top reaches `want`
-        uint32_t mine[8];
-        uint32_t sum = 0;
+                if (e < valid[h] && (key[h][e] & hi_mask) == known)
+                    atomicAdd(&s_hist[(key[h][e] >> shift) & digit_mask], 1u);
+    }
+    __syncthreads();
+}
+
+// For each of NQ ranks (1-based, counted from the highest digit down): the digit whose
+// bin holds that rank, and the rank inside the bin.  s_pick: 2 NQ words.
+template <int NQ>
+__device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const uint32_t* s_hist, uint32_t* s_wave,
+                                            uint32_t* s_pick, uint32_t (&digit)[NQ], uint32_t (&rest)[NQ]) {
+    const int tid = threadIdx.x;
+    // thread t owns the 8 bins 2047-8t .. 2040-8t (descending)
+    uint32_t mine[8];
+    uint32_t sum = 0;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            mine[e] = s_hist[kBins - 1 - (8 * tid + e)];
-            sum += mine[e];
-        }
-        uint32_t total;
-        uint32_t above = block_exclusive_scan(sum, s_wave, &total);
-        if (above < want && want <= above + sum) {
+    for (int e = 0; e < 8; e++) {
+        mine[e] = s_hist[kBins - 1 - (8 * tid + e)];
+        sum += mine[e];
+    }
+    uint32_t total;
+    const uint32_t above = block_exclusive_scan(sum, s_wave, &total);
+#pragma unroll
+    for (int q = 0; q < NQ; q++) {
+        if (above < want[q] && want[q] <= above + sum) {
             uint32_t acc = above;
 #pragma unroll
             for (int e = 0; e < 8; e++) {
-                if (acc < want && want <= acc + mine[e]) {
-                    s_pick[0] = (uint32_t)(kBins - 1 - (8 * tid + e));
-                    s_pick[1] = want - acc;
+                if (acc < want[q] && want[q] <= acc + mine[e]) {
+                    s_pick[2 * q] = (uint32_t)(kBins - 1 - (8 * tid + e));
+                    s_pick[2 * q + 1] = want[q] - acc;
                 }
                 acc += mine[e];
             }
         }
-        __syncthreads();
-        known |= s_pick[0] << shift;
-        want = s_pick[1];
-        __syncthreads();
     }
-    const uint32_t thr = known;     // the k-th largest key
-    const uint32_t take_eq = want;  // how many columns equal to it are kept (the lowest ones)
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NQ; q++) {
+        digit[q] = s_pick[2 * q];
+        rest[q] = s_pick[2 * q + 1];
+    }
+}
 
-    // ---- ordered emission ---------------------------------------------------
+// Radix select: the `rank`-th largest (1-based) among those of the n keys behind `src`
+// that agree with `known` above bit `low_bits`.  Digits of up to 11 bits are resolved
+// from bit low_bits down to bit stop_bits; the result is the selected key with the bits
+// below stop_bits cleared, and *take_eq receives the rank left inside the last bin (with
+// stop_bits = 0: how many keys equal to the result rank at or above it).
+// Called by all 256 threads; s_hist: kBins words, s_wave: 4 words, s_pick: 4 words.
+template <typename Src>
+__device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t rank, uint32_t* s_hist,
+                                                 uint32_t* s_wave, uint32_t* s_pick, uint32_t* take_eq,
+                                                 uint32_t known = 0, int low_bits = 32, int stop_bits = 0) {
+    uint32_t want[1] = {rank};
+    int remaining = low_bits;
+#pragma unroll 1
+    while (remaining > stop_bits) {
+        const int width = min(11, remaining);
+        const int shift = remaining - width;
+        const uint32_t hi_mask = remaining >= 32 ? 0u : ~((1u << remaining) - 1u);
+        digit_histogram(src, n, known, hi_mask, shift, (1u << width) - 1u, s_hist);
+        uint32_t digit[1];
+        pick_digits<1>(want, s_hist, s_wave, s_pick, digit, want);
+        known |= digit[0] << shift;
+        remaining = shift;
+    }
+    __syncthreads();
+    *take_eq = want[0];
+    return known;
+}
+
+// The leading 22 bits of the rank_a-th and of the rank_b-th largest key (low 10 bits
+// cleared).  While both ranks fall into the same bin, one histogram serves both.
+template <typename Src>
+__device__ __forceinline__ void radix_select_pair(const Src& src, int n, uint32_t rank_a, uint32_t rank_b,
+                                                  uint32_t* s_hist, uint32_t* s_wave, uint32_t* s_pick,
+                                                  uint32_t* key_a, uint32_t* key_b) {
+    uint32_t want[2] = {rank_a, rank_b}, digit[2], unused;
+    digit_histogram(src, n, 0u, 0u, 21, 0x7ffu, s_hist);
+    pick_digits<2>(want, s_hist, s_wave, s_pick, digit, want);
+    if (digit[0] == digit[1]) {
+        const uint32_t known = digit[0] << 21;
+        digit_histogram(src, n, known, 0xffe00000u, 10, 0x7ffu, s_hist);
+        pick_digits<2>(want, s_hist, s_wave, s_pick, digit, want);
+        *key_a = known | (digit[0] << 10);
+        *key_b = known | (digit[1] << 10);
+        __syncthreads();
+    } else {
+        *key_a = radix_select(src, n, want[0], s_hist, s_wave, s_pick, &unused, digit[0] << 21, 21, 10);
+        *key_b = radix_select(src, n, want[1], s_hist, s_wave, s_pick, &unused, digit[1] << 21, 21, 10);
+    }
+}
+
+// Ordered emission: every column whose key exceeds thr, and the first take_eq
+// columns whose key equals it, in ascending column order.  One iteration covers
+// 4096 columns: wave w owns columns [1024 w, 1024 w + 1024) of them as four
+// coalesced groups of 256, so one cross-wave exchange serves 16 keys per thread.
+template <typename Src>
+__device__ __forceinline__ void emit_selected(const Src& src, int C, uint32_t thr, uint32_t take_eq,
+                                              int32_t* __restrict__ out, uint32_t* s_wave) {
+    constexpr int U = 4;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int C4 = (C + 3) >> 2;
     uint32_t run_gt = 0, run_eq = 0;
-    for (int base4 = 0; base4 < C4; base4 += 256) {
-        int j4 = base4 + tid;
-        uint32_t key[4] = {0, 0, 0, 0};
-        int valid = 0;
-        if (j4 < C4) valid = keys4(j4, key);
-        uint32_t ngt = 0, neq = 0;
+    for (int base4 = 0; base4 < C4; base4 += 256 * U) {
+        uint32_t key[U][4];
+        int valid[U], j4[U];
+        typename Src::Raw raw[U];
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            if (e < valid) {
-                ngt += key[e] > thr;
-                neq += key[e] == thr;
-            }
+        for (int u = 0; u < U; u++) {
+            j4[u] = base4 + w * (64 * U) + u * 64 + lane;
+            raw[u] = src.load(j4[u]);
         }
-        uint32_t total;
-        uint32_t before = block_exclusive_scan(ngt | (neq << 16), s_wave, &total);
-        uint32_t gt_before = run_gt + (before & 0xffffu);
-        uint32_t eq_before = run_eq + (before >> 16);
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            if (e < valid) {
-                bool gt = key[e] > thr, eq = key[e] == thr;
-                if (gt || (eq && eq_before < take_eq)) out[gt_before + min(eq_before, take_eq)] = 4 * j4 + e;
-                gt_before += gt;
-                eq_before += eq;
+        for (int u = 0; u < U; u++) valid[u] = src.keys(raw[u], j4[u], key[u]);
+        uint32_t cnt[U], inc[U], tot[U], wave_sum = 0;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            uint32_t ngt = 0, neq = 0;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                if (e < valid[u]) {
+                    ngt += key[u][e] > thr;
+                    neq += key[u][e] == thr;
+                }
             }
+            cnt[u] = ngt | (neq << 16);
+            inc[u] = wave_inclusive_scan(cnt[u]);
+            tot[u] = (uint32_t)__builtin_amdgcn_readlane((int)inc[u], 63);
+            wave_sum += tot[u];
+        }
+        __syncthreads();  // s_wave may still be read by the previous iteration
+        if (lane == 0) s_wave[w] = wave_sum;
+        __syncthreads();
+        uint32_t w0 = s_wave[0], w1 = s_wave[1], w2 = s_wave[2], w3 = s_wave[3];
+        uint32_t before = (w > 0 ? w0 : 0u) + (w > 1 ? w1 : 0u) + (w > 2 ? w2 : 0u);
+        uint32_t total = w0 + w1 + w2 + w3;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            uint32_t mine = before + inc[u] - cnt[u];
+            uint32_t gt_before = run_gt + (mine & 0xffffu);
+            uint32_t eq_before = run_eq + (mine >> 16);
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                if (e < valid[u]) {
+                    bool gt = key[u][e] > thr, eq = key[u][e] == thr;
+                    if (gt || (eq && eq_before < take_eq)) out[gt_before + min(eq_before, take_eq)] = 4 * j4[u] + e;
+                    gt_before += gt;
+                    eq_before += eq;
+                }
+            }
+            before += tot[u];
         }
         run_gt += total & 0xffffu;
         run_eq += total >> 16;
     }
+}
+
+// Rows that fit LDS.
+template <bool HAS_PREV>
+__global__ __launch_bounds__(256) void topk_short_rows_kernel(const float* __restrict__ cur,
+                                                              const float* __restrict__ prev, int C, int64_t ld,
+                                                              int k, int32_t* __restrict__ idx,
+                                                              int32_t* __restrict__ counts, int k_stride) {
+    __shared__ uint32_t s_hist[kBins];
+    __shared__ __attribute__((aligned(16))) uint32_t s_keys[kLdsCols];
+    __shared__ uint32_t s_wave[4];
+    __shared__ uint32_t s_pick[4];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    if (tid == 0) counts[row] = k;
+    if (k == 0) return;
+    GlobalRowKeys<HAS_PREV> g{cur + row * ld, HAS_PREV ? prev + row * ld : nullptr, C};
+    const int C4 = (C + 3) >> 2;
+    constexpr int U = 4;
+    for (int base4 = 0; base4 < C4; base4 += 256 * U) {
+        typename GlobalRowKeys<HAS_PREV>::Raw raw[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) raw[u] = g.load(base4 + u * 256 + tid);
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int j4 = base4 + u * 256 + tid;
+            uint32_t key[4];
+            if (g.keys(raw[u], j4, key) > 0)
+                *reinterpret_cast<uint4*>(&s_keys[4 * j4]) = uint4{key[0], key[1], key[2], key[3]};
+        }
+    }
+    LdsKeys src{s_keys, C};
+    uint32_t take_eq;
+    uint32_t thr = radix_select(src, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
+    emit_selected(src, C, thr, take_eq, idx + row * (int64_t)k_stride, s_wave);
+}
+
+// The candidates of a long row whose key equals the threshold, keyed so that the lower column ranks higher.
+struct CandidateTieKeys {
+    const uint32_t* ckey;
+    const uint32_t* ccol;
+    int n;
+    uint32_t thr;
+    struct Raw {
+        uint4 k, c;
+    };
+    __device__ __forceinline__ Raw load(int j4) const {
+        const int j = min(j4, ((n + 3) >> 2) - 1);
+        return Raw{*reinterpret_cast<const uint4*>(ckey + 4 * j), *reinterpret_cast<const uint4*>(ccol + 4 * j)};
+    }
+    __device__ __forceinline__ int keys(const Raw& r, int j4, uint32_t (&key)[4]) const {
+        key[0] = r.k.x == thr ? ~r.c.x : 0u;
+        key[1] = r.k.y == thr ? ~r.c.y : 0u;
+        key[2] = r.k.z == thr ? ~r.c.z : 0u;
+        key[3] = r.k.w == thr ? ~r.c.w : 0u;
+        return max(0, min(4, n - 4 * j4));
+    }
+};
+
+// State of one wave during the single pass over a long row.
+struct LongRowPass {
+    float f_hi, f_lo;         // the pivots, as scores
+    uint32_t* s_mask;         // one bit per column: bit (col & 31) of word col >> 5
+    uint32_t* s_ckey;         // this wave's candidate scores (raw bits) ...
+    uint32_t* s_ccol;         // ... and their columns
+    uint32_t seg_cap;         // slots in this wave's candidate segment
+    uint32_t slot;            // candidates appended so far (the same in every lane)
+    uint32_t n_above;         // per lane: bits set in the mask words this lane wrote
+    int C, G;                 // columns; groups of 256 columns
+};
+
+// One group of 256 columns: lane l holds the scores of columns 256 g + 4 l .. + 3.
+// Lanes 8 j .. 8 j + 7 combine their four "above the upper pivot" bits into mask word
+// 8 g + j; scores between the pivots are appended to the wave's candidates.
+template <bool MASKED>
+__device__ __forceinline__ void long_row_group(LongRowPass& st, const float (&s)[4], int g, int lane) {
+    uint32_t nib = 0;
+    uint64_t cand[4];
+    bool mine[4];
+    const int col0 = (g * 64 + lane) * 4;
+#pragma unroll
+    for (int e = 3; e >= 0; e--) {
+        bool above = s[e] > st.f_hi;
+        bool between = s[e] >= st.f_lo && s[e] <= st.f_hi;
+        if (MASKED) {
+            const bool exists = col0 + e < st.C;
+            above = above && exists;
+            between = between && exists;
+        }
+        nib = nib * 2u + (above ? 1u : 0u);
+        mine[e] = between;
+        cand[e] = __builtin_amdgcn_ballot_w64(between);
+    }
+    uint32_t word = nib << ((lane & 7) * 4);
+    word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x111, 0xf, 0xf, false);  // row_shr:1
+    word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x112, 0xf, 0xf, false);  // row_shr:2
+    word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x114, 0xf, 0xf, false);  // row_shr:4
+    if ((lane & 7) == 7 && (!MASKED || g < st.G)) {
+        st.s_mask[g * 8 + (lane >> 3)] = word;
+        st.n_above += __popc(word);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        if (cand[e] != 0) {
+            uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(cand[e] >> 32),
+                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)cand[e], st.slot));
+            pos = min(pos, st.seg_cap - 1u);  // an overflow is detected from the count
+            if (mine[e]) {
+                st.s_ckey[pos] = __float_as_uint(s[e]);
+                st.s_ccol[pos] = (uint32_t)(col0 + e);
+            }
+            st.slot += (uint32_t)__builtin_popcountll(cand[e]);
+        }
+    }
+}
+
+// Where the threshold is expected among S sampled keys: a rank that very likely lies
+// above it and one that very likely lies below it (1-based from the top; the first may
+// be < 1 and the second > S, which stand for "no such sample").
+__host__ __device__ inline void pivot_ranks(int k, int C, int S, int* rank_hi, int* rank_lo) {
+    const float q = (float)k / (float)C;
+    const float r = q * (float)S;
+    const float margin = kPivotSigmas * sqrtf(fmaxf((float)S * q * (1.f - q), 1.f)) + 2.f;
+    *rank_hi = (int)floorf(r - margin);
+    *rank_lo = (int)ceilf(r + margin) + 1;
+}
+
+// Rows too long for LDS.  With BRACKET the row is read from HBM once:
+//   1. S scores are sampled as segments of 16 consecutive columns; two pivots that bracket
+//      the threshold with 3.5 standard deviations of slack are selected from the sample;
+//   2. one pass over the row records, as a bit per column in LDS, which scores exceed
+//      the upper pivot, and appends the (score, column) pairs between the pivots to LDS
+//      (each wave to a segment of seg_cap slots of its own, so that no atomics are needed);
+//   3. the exact threshold is selected among those candidates and their bits are set;
+//   4. the column indices are written from the bit mask in ascending order.
+// If the bracket misses the threshold or the candidates overflow, or without BRACKET
+// (rows whose mask would not fit LDS), the threshold is selected by three histogram
+// passes over the row in global memory and a fourth pass writes the indices.
+// Dynamic LDS: kBins + 16 words, and with BRACKET max(S, 8 seg_cap + 8 ceil(C / 256)) more.
+template <bool BRACKET, bool HAS_PREV, int S>
+__global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __restrict__ cur,
+                                                             const float* __restrict__ prev, int C, int64_t ld,
+                                                             int k, int32_t* __restrict__ idx,
+                                                             int32_t* __restrict__ counts, int k_stride, int seg_cap) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    uint32_t* s_hist = smem;                // kBins
+    uint32_t* s_wave = smem + kBins;        // 4
+    uint32_t* s_pick = s_wave + 4;          // 4
+    uint32_t* s_seg = s_pick + 4;           // 4: candidates appended by each wave
+    uint32_t* s_above = s_seg + 4;          // 1: scores above the upper pivot
+    uint32_t* s_ckey = smem + kBins + 16;   // 4 seg_cap: candidate scores, later keys (the sample lies here first)
+    uint32_t* s_ccol = s_ckey + 4 * seg_cap;  // 4 seg_cap: candidate columns
+    uint32_t* s_mask = s_ccol + 4 * seg_cap;  // one bit per column
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t row = blockIdx.x;
+    if (tid == 0) counts[row] = k;
+    if (k == 0) return;
+    typedef GlobalRowKeys<HAS_PREV> Row;
+    Row g{cur + row * ld, HAS_PREV ? prev + row * ld : nullptr, C};
+    const int C4 = (C + 3) >> 2;
+    int32_t* out = idx + row * (int64_t)k_stride;
+
+    if constexpr (BRACKET) {
+        // ---- 1. pivots from a sample ---------------------------------------------------------
+        {
+            constexpr int kSegments = S / 16, kPerThread = kSegments / 256;
+            typename Row::Raw raw[kPerThread][4];
+            int start4[kPerThread];
+#pragma unroll
+            for (int j = 0; j < kPerThread; j++) {
+                const int segment = tid * kPerThread + j;
+                start4[j] = (int)(((int64_t)segment * C) / kSegments) >> 4 << 2;  // a multiple of 16 columns
+#pragma unroll
+                for (int v = 0; v < 4; v++) raw[j][v] = g.load(start4[j] + v);
+            }
+#pragma unroll
+            for (int j = 0; j < kPerThread; j++) {
+#pragma unroll
+                for (int v = 0; v < 4; v++) {
+                    uint32_t key[4];
+                    g.keys(raw[j][v], start4[j] + v, key);
+                    *reinterpret_cast<uint4*>(&s_ckey[16 * (tid * kPerThread + j) + 4 * v]) =
+                        uint4{key[0], key[1], key[2], key[3]};
+                }
+            }
+        }
+        if (tid == 0) *s_above = 0;
+        int rank_hi, rank_lo;
+        pivot_ranks(k, C, S, &rank_hi, &rank_lo);
+        LdsKeys sample{s_ckey, S};
+        uint32_t unused;
+        uint32_t pivot_hi = 0xff800000u, pivot_lo = 0x007fffffu;  // keys of +infinity and -infinity
+        // the pivots only have to bracket: 22 leading bits of the sample keys are enough
+        if (rank_hi >= 1 && rank_lo <= S) {
+            radix_select_pair(sample, S, (uint32_t)rank_hi, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &pivot_hi,
+                              &pivot_lo);
+            pivot_hi |= 0x3ffu;
+        } else if (rank_hi >= 1) {
+            pivot_hi = radix_select(sample, S, (uint32_t)rank_hi, s_hist, s_wave, s_pick, &unused, 0u, 32, 10) | 0x3ffu;
+        } else if (rank_lo <= S) {
+            pivot_lo = radix_select(sample, S, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &unused, 0u, 32, 10);
+        }
+        pivot_lo = max(pivot_lo, 1u);
+        __syncthreads();  // the sample is dead from here on
+
+        // ---- 2. one pass over the row ----------------------------------------------------------
+        // A batch is U groups of 256 columns; wave w takes batches w, w + 4, ...  The loads of the
+        // next batch are issued before the current one is consumed.  Batches whose columns all
+        // exist take the unmasked path; the one batch that holds the end of the row is masked.
+        constexpr int U = 8;
+        const int G = (C4 + 63) >> 6;
+        const int full4 = C >> 2;                      // float4 groups that exist completely
+        const int full_batches = full4 / (64 * U);
+        const int last_safe4 = full4 - 64 * U;         // last start from which a whole batch is in bounds
+        LongRowPass st{score_of_key(pivot_hi), score_of_key(pivot_lo), s_mask, s_ckey + w * seg_cap,
+                       s_ccol + w * seg_cap, (uint32_t)seg_cap, 0u, 0u, C, G};
+        const float4* cur4 = reinterpret_cast<const float4*>(g.cur);
+        const float4* prev4 = reinterpret_cast<const float4*>(g.prev);
+        float4 rc[U], rp[U];
+        int b = w;
+        {
+            const int at = min(b * 64 * U, last_safe4);
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                rc[u] = cur4[at + u * 64 + lane];
+                if constexpr (HAS_PREV) rp[u] = prev4[at + u * 64 + lane];
+            }
+        }
+        for (; b < full_batches; b += 4) {
+            float s[U][4];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                if constexpr (HAS_PREV) {
+                    s[u][0] = fabsf(rc[u].x - rp[u].x); s[u][1] = fabsf(rc[u].y - rp[u].y);
+                    s[u][2] = fabsf(rc[u].z - rp[u].z); s[u][3] = fabsf(rc[u].w - rp[u].w);
+                } else {
+                    s[u][0] = rc[u].x; s[u][1] = rc[u].y; s[u][2] = rc[u].z; s[u][3] = rc[u].w;
+                }
+            }
+            const int at = min((b + 4) * 64 * U, last_safe4);
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                rc[u] = cur4[at + u * 64 + lane];
+                if constexpr (HAS_PREV) rp[u] = prev4[at + u * 64 + lane];
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) long_row_group<false>(st, s[u], b * U + u, lane);
+        }
+        if (b == full_batches && b * U < G) {
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                typename Row::Raw raw = g.load((b * U + u) * 64 + lane);  // clamped to the last group
+                float s[4];
+                if constexpr (HAS_PREV) {
+                    s[0] = fabsf(raw.c.x - raw.p.x); s[1] = fabsf(raw.c.y - raw.p.y);
+                    s[2] = fabsf(raw.c.z - raw.p.z); s[3] = fabsf(raw.c.w - raw.p.w);
+                } else {
+                    s[0] = raw.c.x; s[1] = raw.c.y; s[2] = raw.c.z; s[3] = raw.c.w;
+                }
+                long_row_group<true>(st, s, b * U + u, lane);
+            }
+        }
+        if (lane == 0) s_seg[w] = st.slot;
+        if (st.n_above != 0) atomicAdd(s_above, st.n_above);
+        __syncthreads();
+        const uint32_t seg0 = s_seg[0], seg1 = s_seg[1], seg2 = s_seg[2], seg3 = s_seg[3];
+        const uint32_t n_above = *s_above;
+        const uint32_t n_cand = seg0 + seg1 + seg2 + seg3;
+        const bool fits = max(max(seg0, seg1), max(seg2, seg3)) <= (uint32_t)seg_cap;
+
+        if (fits && n_above < (uint32_t)k && (uint32_t)k <= n_above + n_cand) {
+            // ---- 3. exact threshold among the candidates; set the bits of the selected ones --------
+            // Scores become keys relative to the lower pivot, 1 .. span + 1, which need few digits;
+            // the unused slots of every segment get key 0, below every candidate.
+            const int n_slots = 4 * seg_cap;
+            {
+                const uint32_t used = (uint32_t)__builtin_amdgcn_readfirstlane(
+                    (int)(w == 0 ? seg0 : w == 1 ? seg1 : w == 2 ? seg2 : seg3));
+                for (uint32_t i = lane; i < (uint32_t)seg_cap; i += 64) {
+                    uint32_t* slot = st.s_ckey + i;
+                    *slot = i < used ? key_of_score(__uint_as_float(*slot)) - pivot_lo + 1u : 0u;
+                }
+            }
+            const int low_bits = 32 - __clz((int)(pivot_hi - pivot_lo + 1u));
+            uint32_t take_eq;
+            LdsKeys cand{s_ckey, n_slots};
+            const uint32_t thr = radix_select(cand, n_slots, (uint32_t)k - n_above, s_hist, s_wave, s_pick, &take_eq, 0u,
+                                              low_bits);
+            // candidates above the threshold are selected, and so are those equal to it unless there
+            // are more of them than take_eq
+            uint32_t n_eq = 0;
+            for (int i = tid; i < n_slots; i += 256) {
+                const uint32_t key = s_ckey[i], col = s_ccol[i];
+                if (key >= thr) atomicOr(&s_mask[col >> 5], 1u << (col & 31));
+                n_eq += key == thr;
+            }
+            uint32_t n_eq_total;
+            block_exclusive_scan(n_eq, s_wave, &n_eq_total);
+            if (n_eq_total != take_eq) {
+                // ties across the threshold: only the take_eq lowest columns among the equal ones stay
+                CandidateTieKeys ties{s_ckey, s_ccol, n_slots, thr};
+                const uint32_t tie_key = radix_select(ties, n_slots, take_eq, s_hist, s_wave, s_pick, &unused);
+                for (int i = tid; i < n_slots; i += 256) {
+                    const uint32_t key = s_ckey[i], col = s_ccol[i];
+                    if (key == thr && ~col < tie_key) atomicAnd(&s_mask[col >> 5], ~(1u << (col & 31)));
+                }
+            }
+            __syncthreads();
+
+            // ---- 4. indices from the mask, ascending -----------------------------------------------
+            // Wave v owns a quarter of the mask words; per step its lanes take 64 consecutive words,
+            // so neighbouring lanes write neighbouring output slots.
+            const int n_words = 8 * G;
+            const int quarter = (n_words + 3) >> 2;
+            const int q_begin = min(n_words, w * quarter), q_end = min(n_words, q_begin + quarter);
+            uint32_t mine = 0;
+            for (int wi = q_begin + lane; wi < q_end; wi += 64) mine += __popc(s_mask[wi]);
+            uint32_t total;
+            const uint32_t wave_base = block_exclusive_scan(mine, s_wave, &total) - (wave_inclusive_scan(mine) - mine);
+            uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_base);
+            for (int w0 = q_begin; w0 < q_end; w0 += 64) {
+                const int wi = w0 + lane;
+                uint32_t m = wi < q_end ? s_mask[wi] : 0u;
+                const uint32_t inc = wave_inclusive_scan(__popc(m));
+                uint32_t pos = base + inc - __popc(m);
+                base += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+                while (m) {
+                    if (pos < (uint32_t)k) out[pos] = wi * 32 + __ffs((int)m) - 1;
+                    pos++;
+                    m &= m - 1;
+                }
+            }
+            return;
+        }
+    }
+    uint32_t take_eq;
+    const uint32_t thr = radix_select(g, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
+    emit_selected(g, C, thr, take_eq, out, s_wave);
+}
+
+constexpr size_t kMaxLdsBytes = 160 * 1024;
+
+// Launch shape of the single-pass kernel for rows of C columns of which k are kept: the
+// sample size and the candidate slots per wave (1.3 times the expected number plus slack,
+// as far as LDS allows).  Returns false when the column mask leaves no room for candidates.
+struct LongRowPlan {
+    int sample, seg_cap;
+    size_t lds_bytes;
+};
+
+inline bool plan_long_rows(int C, int k, LongRowPlan* plan) {
+    const int S = C >= 65536 ? 8192 : 4096;
+    const size_t mask_words = 8 * (size_t)((C + 255) / 256);
+    const size_t fixed_words = kBins + 16;
+    if ((fixed_words + mask_words + 8 * 128) * 4 > kMaxLdsBytes) return false;
+    int rank_hi, rank_lo;
+    pivot_ranks(k, C, S, &rank_hi, &rank_lo);
+    const double bracket = (double)(std::min(rank_lo, S + 1) - std::max(rank_hi, 0) + 1) / (double)S;
+    const size_t room = (kMaxLdsBytes / 4 - fixed_words - mask_words) / 8;
+    size_t seg_cap = (size_t)(bracket * (double)C * 1.3 / 4.0) + 96;
+    seg_cap = (std::min(std::min(seg_cap, room), (size_t)4096) + 63) / 64 * 64;
+    if (seg_cap > room) seg_cap -= 64;
+    plan->sample = S;
+    plan->seg_cap = (int)seg_cap;
+    plan->lds_bytes = (fixed_words + std::max((size_t)S, 8 * seg_cap + mask_words)) * 4;
+    return true;
 }
 
 }  // namespace chipmunk
@@ -205,11 +678,24 @@ extern "C" int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R
         (reinterpret_cast<uintptr_t>(counts) & 3u))
         return CHIPMUNK_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    if (C <= kLdsCols)
-        hipLaunchKernelGGL((topk_cols_kernel<true>), dim3((unsigned)R), dim3(256), 0, s, cur, prev, C, ld, k, idx,
-                           counts, k_stride);
-    else
-        hipLaunchKernelGGL((topk_cols_kernel<false>), dim3((unsigned)R), dim3(256), 0, s, cur, prev, C, ld, k, idx,
-                           counts, k_stride);
+    const dim3 grid((unsigned)R), block(256);
+    LongRowPlan plan;
+    if (C <= kLdsCols) {
+        auto kernel = prev ? topk_short_rows_kernel<true> : topk_short_rows_kernel<false>;
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, cur, prev, C, ld, k, idx, counts, k_stride);
+    } else if (plan_long_rows(C, k, &plan)) {
+        auto kernel = plan.sample == 8192
+                          ? (prev ? topk_long_rows_kernel<true, true, 8192> : topk_long_rows_kernel<true, false, 8192>)
+                          : (prev ? topk_long_rows_kernel<true, true, 4096> : topk_long_rows_kernel<true, false, 4096>);
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)plan.lds_bytes) != hipSuccess)
+            return CHIPMUNK_ERR_LAUNCH;
+        hipLaunchKernelGGL(kernel, grid, block, plan.lds_bytes, s, cur, prev, C, ld, k, idx, counts, k_stride,
+                           plan.seg_cap);
+    } else {
+        auto kernel = prev ? topk_long_rows_kernel<false, true, 4096> : topk_long_rows_kernel<false, false, 4096>;
+        hipLaunchKernelGGL(kernel, grid, block, (kBins + 16) * sizeof(uint32_t), s, cur, prev, C, ld, k, idx, counts,
+                           k_stride, 0);
+    }
     return launch_status();
 }

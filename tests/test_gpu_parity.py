@@ -83,6 +83,12 @@ def test_voxel_reorder_bit_exact(cm, oracle, geom):
     (12, 4608, 323, False),      # FLUX attention
     (3, 115456, 8082, False),    # HunyuanVideo attention row length
     (3, 75600, 5292, True),
+    (2, 30000, 30000, False),    # long row, k = C
+    (2, 30001, 1, False),        # long row, k = 1, C % 4 != 0
+    (2, 50000, 25000, True),     # long row, half kept: the widest candidate bracket
+    (2, 40000, 39990, False),
+    (1, 800000, 5000, False),    # the column mask takes most of LDS
+    (1, 1300000, 5000, True),    # beyond the single-pass limit: histogram passes over global memory
 ])
 def test_topk_bit_exact(cm, oracle, R, C, k, with_prev):
     g = si.generator(7, DEV)
