@@ -189,7 +189,6 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     constexpr int CH = ROWB / 16;         // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // rows covered by one wave-wide 16-byte load
     constexpr int NI = kTileRows / (RPI * NWAVES);  // such loads per wave per tile and matrix
-    constexpr int NC = NI * RPI;          // tile rows filled by one wave
     constexpr int NT = 64 * NWAVES;
     constexpr int TILE = kTileRows * ROWB;
     constexpr int STAGE = 2 * TILE;       // K tile then V tile
@@ -209,10 +208,6 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const int row0 = chunk * p.c;
     const int rows_valid = min(p.c, p.N - row0);
     const int count = __builtin_amdgcn_readfirstlane(p.counts ? p.counts[unit] : p.N);
-    // The index list is read-only for the whole launch: reading it through the constant
-    // address space lets uniform reads go through the scalar cache.
-    typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
-    const_i32_ptr idxp = p.idx ? (const_i32_ptr)(uintptr_t)(p.idx + unit * (int64_t)p.k_stride) : nullptr;
 
     const int64_t head_off = bh * (int64_t)p.N * E;
     const uint16_t* qh = p.q + head_off;
@@ -262,46 +257,33 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
     const int ntiles = (count + kTileRows - 1) / kTileRows;
 
-    // The selected columns of the tile rows this wave fills are fetched through the
-    // scalar path (the rows of a load are wave-uniform), one step ahead of the gather
-    // that uses them, so the vector-memory counter tracks the asynchronous tile
-    // transfers only.  cols[s][i*RPI + j] belongs to row (i*NWAVES+w)*RPI + j of the
-    // s-th tile of a step.
-    int cols[kTilesPerStep][NC];
-#pragma unroll
-    for (int s = 0; s < kTilesPerStep; s++)
-#pragma unroll
-        for (int x = 0; x < NC; x++) cols[s][x] = 0;
+    // Every lane fetches the selected column of the tile row it fills, one step ahead of
+    // the gather that uses it: the loads are issued behind that step's tile transfers and
+    // have landed, like those, when the next step starts with its wait for all memory.
+    // colv[s][i] belongs to row (i*NWAVES+w)*RPI + sel of the s-th tile of a step.
+    const int32_t* idxg = p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
+    int colv[kTilesPerStep][NI];
     auto load_cols = [&](int tile0) {  // columns of tiles tile0 .. tile0+kTilesPerStep-1
-        const int t0 = __builtin_amdgcn_readfirstlane(tile0);  // keeps the reads below on the scalar path
         const int last = count - 1;
 #pragma unroll
         for (int s = 0; s < kTilesPerStep; s++)
 #pragma unroll
-            for (int i = 0; i < NI; i++)
+            for (int i = 0; i < NI; i++) colv[s][i] = min((tile0 + s) * kTileRows + (i * NWAVES + w) * RPI + sel, last);
+        if (idxg) {
 #pragma unroll
-                for (int j = 0; j < RPI; j++) {
-                    int pos = min((t0 + s) * kTileRows + (i * NWAVES + wu) * RPI + j, last);
-                    cols[s][i * RPI + j] = idxp ? idxp[pos] : pos;
-                }
+            for (int s = 0; s < kTilesPerStep; s++)
+#pragma unroll
+                for (int i = 0; i < NI; i++) colv[s][i] = idxg[colv[s][i]];
+        }
     };
-    auto pick4 = [&](int a0, int a1, int a2, int a3, int which) -> int {
-        int lo = which & 1 ? a1 : a0, hi = which & 1 ? a3 : a2;
-        return which & 2 ? hi : lo;
-    };
-    auto gather = [&](int half) {  // fills buffers half*kTilesPerStep .. with the tiles whose columns are in cols
+    auto gather = [&](int half) {  // fills buffers half*kTilesPerStep .. with the tiles whose columns are in colv
 #pragma unroll
         for (int s = 0; s < kTilesPerStep; s++)
 #pragma unroll
             for (int i = 0; i < NI; i++) {
-                int col = pick4(cols[s][i * RPI], cols[s][i * RPI + 1], cols[s][i * RPI + 2], cols[s][i * RPI + 3], sel & 3);
-                if (RPI == 8) {
-                    int hi = pick4(cols[s][i * RPI + 4], cols[s][i * RPI + 5], cols[s][i * RPI + 6], cols[s][i * RPI + 7], sel & 3);
-                    col = sel & 4 ? hi : col;
-                }
                 int row = (i * NWAVES + w) * RPI + sel;
                 // byte offset of this lane's chunk inside the head's K (and V) matrix
-                uint32_t goff = (uint32_t)col * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
+                uint32_t goff = (uint32_t)colv[s][i] * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
                 uint32_t dst = lds0 + (uint32_t)((half * kTilesPerStep + s) * STAGE + i * NWAVES * 1024);
                 load_global_to_lds_16B(kh, goff, dst);
                 load_global_to_lds_16B(vh, goff, dst + TILE);
@@ -314,6 +296,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
 
     // first step in flight; columns of the second step requested
     load_cols(0);
+    wait_all_memory();
     gather(0);
     load_cols(kTilesPerStep);
 
