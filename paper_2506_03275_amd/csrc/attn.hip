@@ -97,7 +97,10 @@ __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<
 }
 
 // Raise the reference max where this tile's scores exceed it by more than the
-// slack; O and the denominator are rescaled (rare after the first tiles).
+// slack; O and the denominator are rescaled (rare after the first tiles).  The
+// common case costs a lane only the max over its own 8 scores per query block:
+// the reduction over the four lanes that share a query runs when some lane of
+// the wave has seen an excess.
 template <int E, int NQB>
 __device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB], float sl2) {
     float mx[NQB];
@@ -106,13 +109,13 @@ __device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, const f32
     for (int qb = 0; qb < NQB; qb++) {
         float a = fmaxf(fmaxf(S[0][qb][0], S[0][qb][1]), fmaxf(S[0][qb][2], S[0][qb][3]));
         float b = fmaxf(fmaxf(S[1][qb][0], S[1][qb][1]), fmaxf(S[1][qb][2], S[1][qb][3]));
-        mx[qb] = rows4_max(fmaxf(a, b)) * sl2;
+        mx[qb] = fmaxf(a, b) * sl2;
         need |= mx[qb] > st.m2[qb] + kRescaleSlack;
     }
     if (__builtin_amdgcn_ballot_w64(need) != 0) {
 #pragma unroll
         for (int qb = 0; qb < NQB; qb++) {
-            float mnew = fmaxf(st.m2[qb], mx[qb]);
+            float mnew = fmaxf(st.m2[qb], rows4_max(mx[qb]));
             float alpha = __builtin_amdgcn_exp2f(st.m2[qb] - mnew);
             st.m2[qb] = mnew;
             st.L[qb] *= alpha;
