@@ -35,6 +35,17 @@ import synth_inputs as si  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
+CALIBRATION_COPY_BYTES = 256 << 20
+
+# HBM-side bytes of one attn_sparse_delta_kernel launch (reads + writes beyond L2), from two
+# `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE), each counter scaled by what it
+# read for the --traffic-calibration copy of known size; the summaries with the commands are
+# profiles/attn_sparse_delta_traffic_<workload>.txt.  A counter run cannot happen inside this
+# process, so the figure is carried here and reported with the live timing.
+MEASURED_ATTN_TRAFFIC_BYTES = {
+    "flux": 2.0 * 67358 * 1024 + 1.0 * 28830 * 1024,
+    "hunyuan": 2.0 * 12620292 * 1024 + 1.0 * 721739 * 1024,
+}
 
 WORKLOAD_TEXT = {
     "tiny": "Tiny: 1024 tokens (8x8x16 grid), 2 heads x 64, MLP 256->1024, chunk 128, keep 25%",
@@ -242,6 +253,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also launch a plain elementwise copy of 256 MiB (untimed), the known-size kernel that "
+                         "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path has no collectives; sharding is a design "
@@ -259,6 +273,14 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     st = build_state(cm, args.workload, args.attn_keep, args.mlp_keep, args.seed, dev)
+
+    if args.traffic_calibration:
+        src = torch.ones(CALIBRATION_COPY_BYTES // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)   # reads and writes CALIBRATION_COPY_BYTES each
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(warmup):
         sparse_step(cm, st)
@@ -280,7 +302,8 @@ def main():
     achieved = fl_attn / (attn_ms * 1e-3) / 1e12
     roofline = {"kernel": "attn_sparse_delta_kernel", "bound": "mfma", "achieved": achieved,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": None, "launch_ms": attn_ms, "algorithmic_flops_per_launch": fl_attn}
+                "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.workload) if args.attn_keep is None else None,
+                "launch_ms": attn_ms, "algorithmic_flops_per_launch": fl_attn}
 
     extra = {"stage_ms": stages,
              "attn_useful_tflops": achieved,

@@ -305,10 +305,13 @@ __global__ __launch_bounds__(256) void topk_short_rows_kernel(const float* __res
                                                               const float* __restrict__ prev, int C, int64_t ld,
                                                               int k, int32_t* __restrict__ idx,
                                                               int32_t* __restrict__ counts, int k_stride) {
-    __shared__ uint32_t s_hist[kBins];
-    __shared__ __attribute__((aligned(16))) uint32_t s_keys[kLdsCols];
-    __shared__ uint32_t s_wave[4];
-    __shared__ uint32_t s_pick[4];
+    // dynamic LDS, sized to the row so that short rows leave room for more workgroups per CU:
+    // kBins + 8 words, then the row's keys (a multiple of four)
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    uint32_t* s_hist = smem;
+    uint32_t* s_wave = smem + kBins;
+    uint32_t* s_pick = s_wave + 4;
+    uint32_t* s_keys = smem + kBins + 8;
     const int tid = threadIdx.x;
     const int64_t row = blockIdx.x;
     if (tid == 0) counts[row] = k;
@@ -682,7 +685,8 @@ extern "C" int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R
     LongRowPlan plan;
     if (C <= kLdsCols) {
         auto kernel = prev ? topk_short_rows_kernel<true> : topk_short_rows_kernel<false>;
-        hipLaunchKernelGGL(kernel, grid, block, 0, s, cur, prev, C, ld, k, idx, counts, k_stride);
+        const size_t lds = (kBins + 8 + (size_t)((C + 3) / 4) * 4) * sizeof(uint32_t);
+        hipLaunchKernelGGL(kernel, grid, block, lds, s, cur, prev, C, ld, k, idx, counts, k_stride);
     } else if (plan_long_rows(C, k, &plan)) {
         auto kernel = plan.sample == 8192
                           ? (prev ? topk_long_rows_kernel<true, true, 8192> : topk_long_rows_kernel<true, false, 8192>)
