@@ -88,6 +88,19 @@ def _ptr(t, dtype, name):
     return t.data_ptr()
 
 
+def _ptr_rows(t, dtype, name):
+    """A [R, C] tensor whose rows are dense but may be spaced by a leading dimension larger than C."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or t.dtype != dtype or t.dim() != 2:
+        raise TypeError(f"{name}: expected a 2-D torch tensor of {dtype}")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must live on the GPU")
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise ValueError(f"{name}: rows must be dense")
+    return t.data_ptr()
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -110,9 +123,12 @@ def voxel_reorder(src, dst, perm, inv_perm, n_prefix, T, H, W, n_suffix, vt, vh,
 
 
 def topk_cols(cur, prev, k, idx, counts):
-    """cur, prev: fp32 [R, C] (prev may be None); idx: int32 [R, k_stride]; counts: int32 [R]."""
+    """cur, prev: fp32 [R, C] with dense rows and one common row stride (prev may be None); idx: int32
+    [R, k_stride]; counts: int32 [R]."""
     R, C = cur.shape
-    _check(load().chipmunk_topk_cols(_ptr(cur, torch.float32, "cur"), _ptr(prev, torch.float32, "prev"), R, C,
+    if prev is not None and (prev.shape != cur.shape or prev.stride(0) != cur.stride(0)):
+        raise ValueError("prev must have the shape and row stride of cur")
+    _check(load().chipmunk_topk_cols(_ptr_rows(cur, torch.float32, "cur"), _ptr_rows(prev, torch.float32, "prev"), R, C,
                                      cur.stride(0), k, _ptr(idx, torch.int32, "idx"),
                                      _ptr(counts, torch.int32, "counts"), idx.shape[-1], _stream()),
            "chipmunk_topk_cols")

@@ -155,3 +155,31 @@ def np_f32(t):
 def np_bf16_round(a):
     """float array -> float32 array whose values are exactly representable in bf16 (RNE)."""
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).float().numpy()
+
+
+def stack_inputs(cfg, n_blocks, n_steps, seed, device="cpu"):
+    """Inputs of a stack of DiT blocks over consecutive diffusion steps (BASELINE config 4).
+
+    Returns blocks[b] = dict(q, k, v, x: lists over steps of bf16 tensors; w1, b1, w2, b2).  Every block has its
+    own draws; step t+1 is step t perturbed by the recipe above with the block's fixed set of hot key tokens.
+    The blocks' inputs are independent of each other's outputs: projections and modulation between blocks are
+    dense operations outside the method and are not modelled.
+    """
+    B, H, E, D, F = cfg["B"], cfg["H"], cfg["E"], cfg["D"], cfg["F"]
+    N = config_tokens(cfg)
+    blocks = []
+    for b in range(n_blocks):
+        g = generator(seed + 7919 * (b + 1), device)
+        q = [randn_bf16((B, H, N, E), g)]
+        k = [randn_bf16((B, H, N, E), g)]
+        v = [randn_bf16((B, H, N, E), g)]
+        x = [randn_bf16((B, N, D), g)]
+        hot = hot_mask(N, g)
+        for _ in range(1, n_steps):
+            k.append(perturb_rows(k[-1], hot, g))
+            v.append(perturb_rows(v[-1], hot, g))
+            q.append(perturb_all(q[-1], g))
+            x.append(perturb_all(x[-1], g))
+        w1, b1, w2, b2 = mlp_weights(D, F, seed + 7919 * (b + 1), device)
+        blocks.append(dict(q=q, k=k, v=v, x=x, w1=w1, b1=b1, w2=w2, b2=b2))
+    return blocks

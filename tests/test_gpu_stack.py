@@ -1,0 +1,90 @@
+"""The layer stack of BASELINE config 4 at a small shape: two blocks over three diffusion steps (one dense, two
+column-sparse), with and without the side-stream overlap of the MLP index work, against the oracle chained the
+same way.  The oracle takes its index lists from the GPU run (top-k parity has its own bit-exact tests on a shared
+score buffer; here a borderline column chosen differently from slightly different scores would change what is
+compared), everything else it computes itself in fp64 from the same bf16 inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from parity import REL_TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def _run_gpu(cm, cfg, inputs, k_a, k_m, overlap):
+    from paper_2506_03275_amd import stack
+    blocks = [stack.Block(inp, cfg["c"], k_a, k_m) for inp in inputs]
+    stack.dense_step(blocks, 0)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream() if overlap else None
+    record = {}
+    for step in (1, 2):
+        def grab(b, blk, step=step):
+            # enqueue copies on the main stream: they see this block's results, not later ones
+            record[(step, b)] = (blk.attn_out.clone(), blk.m_cache.clone(), blk.idx_m.clone(), blk.cnt_m.clone())
+        stack.sparse_step(blocks, step, side, grab)
+    torch.cuda.synchronize()
+    return blocks, record
+
+
+@pytest.mark.parametrize("overlap", [False, True])
+def test_stack_matches_chained_oracle(oracle, overlap):
+    import paper_2506_03275_amd as cm
+    cm.load()
+    cfg = si.CONFIGS["tiny"]
+    c, E = cfg["c"], cfg["E"]
+    N = si.config_tokens(cfg)
+    k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
+    inputs = si.stack_inputs(cfg, 2, 3, 5, DEV)
+    blocks, record = _run_gpu(cm, cfg, inputs, k_a, k_m, overlap)
+    scale, act = 1.0 / math.sqrt(E), cm.ACT_GELU_TANH
+    f32 = si.np_f32
+    for b, (blk, inp) in enumerate(zip(blocks, inputs)):
+        idx_a, cnt_a = blk.idx_a.cpu().numpy(), blk.cnt_a.cpu().numpy()
+        # dense step
+        q, k, v, x = (f32(inp[n][0]) for n in "qkvx")
+        w1, b1, w2, b2 = (f32(inp[n]) for n in ("w1", "b1", "w2", "b2"))
+        o_dense = oracle.attn_dense(q, k, v, c, scale)
+        o_cache = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, o_dense, c, scale, -1.0)
+        cache_gpu = f32(blk.o_cache).astype(np.float64)
+        assert rel_err(cache_gpu, o_cache) <= REL_TOL, (overlap, b)
+        m_cache, a_cache, T_m = oracle.mlp_dense(x, w1, b1, w2, b2, c, act, a_ld=blk.a_cache.shape[-1])
+        for step in (1, 2):
+            g_attn, g_mlp, g_idx, g_cnt = record[(step, b)]
+            q, k, v, x = (f32(inp[n][step]) for n in "qkvx")
+            # out = cache + delta where the two nearly cancel: the delta is what the kernel computes and what
+            # the tolerance applies to, so the oracle adds its delta to the call's own bf16 cache
+            ref = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, cache_gpu, c, scale, 1.0)
+            assert rel_err(f32(g_attn) - cache_gpu, ref - cache_gpu) <= REL_TOL, (overlap, b, step)
+            # the GPU's index choice must be the exact top-k of the GPU's own scores
+            T_gpu = torch.empty_like(blk.T)
+            cm.mlp_tile_mean_preact(inp["x"][step], inp["w1"], T_gpu, c, blk.ws_tm)
+            ref_idx, ref_cnt = oracle.topk_cols(T_gpu.view(-1, cfg["F"]).cpu().numpy(),
+                                                blk.T_m.view(-1, cfg["F"]).cpu().numpy(), k_m)
+            assert np.array_equal(g_idx.view(-1, k_m).cpu().numpy(), ref_idx), (overlap, b, step)
+            assert np.array_equal(g_cnt.view(-1).cpu().numpy(), ref_cnt)
+            assert rel_err(T_gpu.cpu().numpy(), oracle.mlp_tile_scores(x, w1, c)) <= 1e-3
+            oracle.mlp_sparse_delta(x, w1, b1, w2, g_idx.cpu().numpy(), g_cnt.cpu().numpy(), a_cache, m_cache, c, act)
+            assert rel_err(f32(g_mlp), m_cache) <= REL_TOL, (overlap, b, step)
+        assert rel_err(f32(blk.a_cache), a_cache) <= REL_TOL
+
+
+def test_stack_overlap_equals_serial():
+    """The two schedules enqueue the same kernels on the same data: results must agree bit for bit."""
+    import paper_2506_03275_amd as cm
+    cm.load()
+    cfg = si.CONFIGS["tiny"]
+    N = si.config_tokens(cfg)
+    k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
+    inputs = si.stack_inputs(cfg, 3, 3, 9, DEV)
+    _, serial = _run_gpu(cm, cfg, inputs, k_a, k_m, False)
+    _, overlapped = _run_gpu(cm, cfg, inputs, k_a, k_m, True)
+    for key in serial:
+        for a, b in zip(serial[key], overlapped[key]):
+            assert torch.equal(a, b), key
