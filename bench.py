@@ -14,7 +14,11 @@ column) attention interactions and (chunk, hidden column) MLP interactions,
 4*E*rows*count per attention unit and 4*D*rows*count per MLP unit, divided by
 the whole step's time.  Softmax, GELU, index work and padding count as zero.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flux|hunyuan|wan|tiny]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload hunyuan|flux|wan|tiny|stack]
+
+The default workload is the HunyuanVideo-shaped configuration at 93 % column sparsity of attention and MLP: the
+sparsity the headline metric is quoted at (the FLUX-shaped configuration keeps 10 % of the hidden columns, and the
+paper's 9.3x kernel figure is for this sequence length).
 
 prints ONE JSON line.  Nothing here runs on more than one GPU.
 """
@@ -316,7 +320,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="flux", choices=sorted(si.CONFIGS) + ["stack"])
+    ap.add_argument("--workload", default="hunyuan", choices=sorted(si.CONFIGS) + ["stack"])
     ap.add_argument("--attn-keep", type=float, default=None, help="fraction of key columns kept (default: the config's)")
     ap.add_argument("--mlp-keep", type=float, default=None, help="fraction of hidden columns kept")
     ap.add_argument("--seed", type=int, default=0)
