@@ -326,6 +326,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--index-structures", action="store_true",
+                    help="also time the attention kernel alone on two other index structures of the same size: "
+                         "columns drawn uniformly per chunk, and whole blocks of 128 consecutive columns")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch a plain elementwise copy of 256 MiB (untimed), the known-size kernel that "
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -384,6 +387,27 @@ def main():
     extra = {"stage_ms": stages,
              "attn_useful_tflops": achieved,
              "mlp_useful_tflops": fl_mlp / (stages["mlp_sparse_delta"] * 1e-3) / 1e12}
+    if args.index_structures:
+        R = st["B"] * st["H"] * st["NB"]
+        kinds = {"topk_of_column_sums": (st["idx_a"], st["cnt_a"])}
+        iu, cu = si.uniform_indices(R, st["N"], st["k_a"], args.seed, dev)
+        kinds["uniform_per_chunk"] = (iu.view(st["B"], st["H"], st["NB"], -1), cu.view(st["B"], st["H"], st["NB"]))
+        ib, cb = si.block_indices(R, st["N"], st["k_a"], 128, args.seed, dev)
+        kinds["blocks_of_128_columns"] = (ib.view(st["B"], st["H"], st["NB"], -1), cb.view(st["B"], st["H"], st["NB"]))
+        extra["attn_index_structures"] = {}
+        for kind, (idx, cnt) in kinds.items():
+            t = Timer()
+            for i in range(4):
+                a, b = t.span("k") if i else Timer().span("warm")
+                a.record()
+                cm.attn_sparse_delta(st["q"], st["k"], st["v"], idx, cnt, st["o_cache_attn"], st["o_attn"], st["c"],
+                                     st["scale"], 1.0)
+                b.record()
+            torch.cuda.synchronize()
+            ms = t.mean_ms("k")
+            extra["attn_index_structures"][kind] = {"ms": ms, "useful_tflops": fl_attn / (ms * 1e-3) / 1e12}
+        del kinds, iu, ib
+
     if not args.no_dense:
         st["dense_out"] = torch.empty_like(st["x"])
         st["dense_a"] = torch.empty_like(st["a_cache"])

@@ -183,3 +183,20 @@ def stack_inputs(cfg, n_blocks, n_steps, seed, device="cpu"):
         w1, b1, w2, b2 = mlp_weights(D, F, seed + 7919 * (b + 1), device)
         blocks.append(dict(q=q, k=k, v=v, x=x, w1=w1, b1=b1, w2=w2, b2=b2))
     return blocks
+
+
+def block_indices(R, C, k, block, seed, device="cpu"):
+    """k columns per row as whole runs of `block` consecutive, block-aligned columns drawn uniformly (the last run is
+    cut so that exactly k columns remain), ascending: idx [R, k] int32, counts [R].  Stands for a [c, block]
+    block-sparse pattern expressed as a column list."""
+    g = generator(seed + 5000003, device)
+    n_blocks_total = -(-C // block)
+    n_pick = min(n_blocks_total, -(-k // block) + 1)
+    keys = torch.rand((R, n_blocks_total), generator=g, device=device)
+    picked = keys.argsort(dim=1)[:, :n_pick].sort(dim=1).values                      # [R, n_pick] block numbers
+    cols = (picked.unsqueeze(-1) * block + torch.arange(block, device=device)).reshape(R, -1)
+    cols = torch.where(cols < C, cols, torch.full_like(cols, C))                     # the last block may be ragged
+    cols = cols.sort(dim=1).values[:, :k]
+    assert int(cols.max()) < C, "not enough columns in the picked blocks"
+    counts = torch.full((R,), k, dtype=torch.int32, device=device)
+    return cols.to(torch.int32).contiguous(), counts
