@@ -334,8 +334,8 @@ def main():
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the hot path has no collectives; sharding is a design "
-              "note in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the hot path has no collectives: every (batch, head, chunk) "
+              "unit is independent and would shard without exchange). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback.", file=sys.stderr)
