@@ -11,6 +11,8 @@ from .chipmunk_oracle import (  # noqa: F401
     topk_cols,
     attn_dense,
     attn_sparse_delta,
+    attn_row_stats,
+    attn_colsum_stale,
     mlp_dense,
     mlp_tile_scores,
     mlp_sparse_delta,

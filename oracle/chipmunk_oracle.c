@@ -195,6 +195,70 @@ int oracle_attn_dense(const float* q, const float* k, const float* v, double* ou
     return err ? -8 : 0;
 }
 
+/* Row statistics of dense attention: m[b,h,n] = max_j scale*<Q_n,K_j> and
+ * l[b,h,n] = sum_j exp(scale*<Q_n,K_j> - m[b,h,n]), the softmax normalisers that
+ * Alg. 4 carries from one step to the next (prev_m, prev_l).
+ */
+int oracle_attn_row_stats(const float* q, const float* k, double* m_out, double* l_out,
+                          int B, int H, int Nq, int Nk, int E, double scale) {
+    if (B < 1 || H < 1 || Nq < 1 || Nk < 1 || E < 1) return -2;
+    int64_t rows = (int64_t)B * H * Nq;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < rows; n++) {
+        int64_t bh = n / Nq;
+        const float* qr = q + n * E;
+        const float* kk = k + bh * Nk * E;
+        double m = -INFINITY;
+        for (int j = 0; j < Nk; j++) {
+            double s = 0.0;
+            for (int e = 0; e < E; e++) s += (double)qr[e] * (double)kk[(int64_t)j * E + e];
+            s *= scale;
+            if (s > m) m = s;
+        }
+        double l = 0.0;
+        for (int j = 0; j < Nk; j++) {
+            double s = 0.0;
+            for (int e = 0; e < E; e++) s += (double)qr[e] * (double)kk[(int64_t)j * E + e];
+            l += exp(scale * s - m);
+        }
+        m_out[n] = m;
+        l_out[n] = l;
+    }
+    return 0;
+}
+
+/* Column sums with given (stale) normalisers (Alg. 4; App. B.2):
+ *   p_approx[n,j] = exp(scale*<Q_n,K_j> - prev_m[n]) / prev_l[n],
+ *   cs[b,h,i,j]   = sum over the rows n of chunk i of p_approx[n,j].
+ * prev_m, prev_l are [B,H,Nq]; cs is [B,H,ceil(Nq/c),Nk].
+ */
+int oracle_attn_colsum_stale(const float* q, const float* k, const double* prev_m,
+                             const double* prev_l, double* cs, int B, int H, int Nq, int Nk,
+                             int E, int c, double scale) {
+    if (B < 1 || H < 1 || Nq < 1 || Nk < 1 || E < 1 || c < 1) return -2;
+    int NB = (Nq + c - 1) / c;
+    int64_t units = (int64_t)B * H * NB;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; u++) {
+        int64_t bh = u / NB;
+        int i = (int)(u % NB);
+        const float* kk = k + bh * Nk * E;
+        double* row = cs + u * Nk;
+        for (int j = 0; j < Nk; j++) row[j] = 0.0;
+        int r1 = (i + 1) * c < Nq ? (i + 1) * c : Nq;
+        for (int r = i * c; r < r1; r++) {
+            const float* qr = q + (bh * Nq + r) * E;
+            double m = prev_m[bh * Nq + r], l = prev_l[bh * Nq + r];
+            for (int j = 0; j < Nk; j++) {
+                double s = 0.0;
+                for (int e = 0; e < E; e++) s += (double)qr[e] * (double)kk[(int64_t)j * E + e];
+                row[j] += exp(scale * s - m) / l;
+            }
+        }
+    }
+    return 0;
+}
+
 /* Column-sparse delta attention (Sec. 3.3.1 "Sparse Delta Steps"; Alg. 3).
  * For chunk i of (b,h) with S = idx[b,h,i,0:counts[b,h,i]] and each of its
  * rows q:

@@ -47,6 +47,8 @@ def _load():
             "oracle_topk_cols": [_ptr, _ptr, _i32, _i32, _i64, _i32, _ptr, _ptr, _i32],
             "oracle_attn_dense": [_ptr] * 5 + [_i32] * 6 + [_f64],
             "oracle_attn_sparse_delta": [_ptr] * 7 + [_i32] * 7 + [_f64, _f64],
+            "oracle_attn_row_stats": [_ptr] * 4 + [_i32] * 5 + [_f64],
+            "oracle_attn_colsum_stale": [_ptr] * 5 + [_i32] * 6 + [_f64],
             "oracle_mlp_dense": [_ptr] * 7 + [_i64, _ptr] + [_i32] * 6,
             "oracle_mlp_tile_scores": [_ptr] * 3 + [_i32] * 5,
             "oracle_mlp_sparse_delta": [_ptr] * 7 + [_i64, _ptr] + [_i32] * 7,
@@ -128,6 +130,35 @@ def attn_dense(q, k, v, c, scale, want_colsum=False):
     _check(_load().oracle_attn_dense(_p(q), _p(k), _p(v), _p(out), _p(D), B, H, Nq, Nk, E, c, float(scale)),
            "oracle_attn_dense")
     return (out, D) if want_colsum else out
+
+
+def attn_row_stats(q, k, scale):
+    """q [B,H,Nq,E], k [B,H,Nk,E] float32 -> (m, l) float64 [B,H,Nq]: row max of the scaled scores and
+    sum_j exp(score - m).  The normalisers Alg. 4 carries between steps."""
+    _arr(q, np.float32, None, "q")
+    B, H, Nq, E = q.shape
+    Nk = k.shape[2]
+    _arr(k, np.float32, (B, H, Nk, E), "k")
+    m = np.empty((B, H, Nq), np.float64)
+    l = np.empty((B, H, Nq), np.float64)
+    _check(_load().oracle_attn_row_stats(_p(q), _p(k), _p(m), _p(l), B, H, Nq, Nk, E, float(scale)),
+           "oracle_attn_row_stats")
+    return m, l
+
+
+def attn_colsum_stale(q, k, prev_m, prev_l, c, scale):
+    """cs[b,h,i,j] = sum over the rows n of chunk i of exp(scale q_n.k_j - prev_m[n]) / prev_l[n].  Alg. 4."""
+    _arr(q, np.float32, None, "q")
+    B, H, Nq, E = q.shape
+    Nk = k.shape[2]
+    _arr(k, np.float32, (B, H, Nk, E), "k")
+    _arr(prev_m, np.float64, (B, H, Nq), "prev_m")
+    _arr(prev_l, np.float64, (B, H, Nq), "prev_l")
+    NB = -(-Nq // c)
+    cs = np.empty((B, H, NB, Nk), np.float64)
+    _check(_load().oracle_attn_colsum_stale(_p(q), _p(k), _p(prev_m), _p(prev_l), _p(cs), B, H, Nq, Nk, E, c,
+                                            float(scale)), "oracle_attn_colsum_stale")
+    return cs
 
 
 def attn_sparse_delta(q, k, v, idx, counts, base, c, scale, o_scale):

@@ -142,6 +142,42 @@ def test_sparse_delta_order_of_S_and_cache_roundtrip(oracle):
     assert not np.allclose(out_sw[0, 0, :2 * c], out[0, 0, :2 * c], atol=1e-6)
 
 
+def test_row_stats_and_stale_column_sums(oracle):
+    """Alg. 4: p_approx = exp(qk - prev_m) / prev_l summed over each chunk's rows.
+    Pins: the statistics against torch.logsumexp (m + log l is the row's log-sum-exp, whatever reference m is used);
+    with the current step's own statistics the sums are the exact column sums D of the dense step (softmax from
+    torch); any other valid reference pair (m - d, l e^d) gives the same sums; doubling prev_l halves them; and
+    with step-1 statistics on step-2 inputs the sums equal torch's exp/sum written from the definition."""
+    B, H, N, E, c = 2, 2, 70, 16, 32
+    q, k = _rand((B, H, N, E), 21), _rand((B, H, N, E), 22)
+    scale = 1.0 / math.sqrt(E)
+    m, l = oracle.attn_row_stats(q, k, scale)
+    S = _t64(q) @ _t64(k).transpose(-1, -2) * scale
+    assert np.allclose(m, S.max(dim=-1).values.numpy(), rtol=0, atol=1e-12)
+    assert np.allclose(m + np.log(l), torch.logsumexp(S, dim=-1).numpy(), rtol=0, atol=1e-12)
+    NB = -(-N // c)
+    P = torch.softmax(S, dim=-1).numpy()
+    D_def = np.stack([P[:, :, i * c:(i + 1) * c].sum(axis=2) for i in range(NB)], axis=2)
+    cs = oracle.attn_colsum_stale(q, k, m, l, c, scale)
+    assert cs.shape == (B, H, NB, N)
+    assert np.allclose(cs, D_def, rtol=0, atol=1e-12)
+    _, D = oracle.attn_dense(q, k, _rand((B, H, N, E), 23), c, scale, want_colsum=True)
+    assert np.allclose(cs, D, rtol=0, atol=1e-12)
+    assert np.allclose(oracle.attn_colsum_stale(q, k, m - 1.5, l * math.exp(1.5), c, scale), cs, rtol=1e-12, atol=0)
+    assert np.allclose(oracle.attn_colsum_stale(q, k, m, 2.0 * l, c, scale), 0.5 * cs, rtol=1e-12, atol=0)
+    # stale statistics: step-2 inputs with the step-1 normalisers
+    q2 = q + _rand((B, H, N, E), 24, 0.05)
+    k2 = k + _rand((B, H, N, E), 25, 0.05)
+    S2 = _t64(q2) @ _t64(k2).transpose(-1, -2) * scale
+    approx = (torch.exp(S2 - _t64(m).unsqueeze(-1)) / _t64(l).unsqueeze(-1)).numpy()
+    ref = np.stack([approx[:, :, i * c:(i + 1) * c].sum(axis=2) for i in range(NB)], axis=2)
+    got = oracle.attn_colsum_stale(q2, k2, m, l, c, scale)
+    assert np.allclose(got, ref, rtol=1e-12, atol=0)
+    assert not np.allclose(got, cs, rtol=1e-3, atol=0)   # the stale sums are an approximation, not D itself
+    # a transposed operand (k, q swapped) must show: rows and columns are different axes
+    assert not np.allclose(oracle.attn_colsum_stale(k, q, m, l, c, scale), cs, rtol=1e-3, atol=0)
+
+
 def test_sparse_delta_rejects_bad_indices(oracle):
     q, k, v, idx, counts, base, c, scale = _sparse_setup()
     bad = idx.copy()
