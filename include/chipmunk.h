@@ -100,11 +100,30 @@ size_t chipmunk_attn_dense_workspace_bytes(int B, int H, int N);
  * the stale-constant approximation of App. B.2): a first pass writes each row's
  * softmax statistics into ws, a second pass recomputes the scores and sums the
  * normalised probabilities per chunk.  ws (chipmunk_attn_dense_workspace_bytes)
- * is needed only when colsum != NULL; its contents are undefined afterwards. */
+ * is needed only when colsum != NULL.  Afterwards it holds those statistics as
+ * two fp32 arrays [B,H,N]: m, the reference each row's exponentials were taken
+ * against (in units of the scaled scores; within 2^8 of the row maximum, not
+ * necessarily equal to it), then l = sum_j exp(score_j - m): the pair a later
+ * step can hand to chipmunk_attn_colsum_stale as (prev_m, prev_l). */
 int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                             uint16_t* out, float* colsum, int64_t ld_colsum,
                             int B, int H, int N, int E, int c, float softmax_scale,
                             void* ws, size_t ws_bytes, void* stream);
+
+/* Column sums with given normalisers (Alg. 4; App. B.2: the normalisers of the
+ * previous diffusion step stand in for the current ones):
+ *   colsum[b,h,i,j] = sum over the rows n of chunk i of
+ *                     exp(softmax_scale * <q[n],k[j]> - prev_m[n]) / prev_l[n].
+ * With the statistics of the same q, k (as left in the workspace of
+ * chipmunk_attn_dense) these are the exact column sums D; with statistics of
+ * an earlier step they are the paper's approximation, meant only to rank
+ * columns.  q, k: [B,H,N,E] bf16; prev_m, prev_l: [B,H,N] fp32; colsum:
+ * [B,H,NB,ld_colsum] fp32 (ld_colsum >= N, multiple of 4; columns N..ld-1 are
+ * left untouched).  Scores far above prev_m overflow to +inf like the formula
+ * does.  E in {64,128}; c in {128,192}. */
+int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t* k, const float* prev_m,
+                                   const float* prev_l, float* colsum, int64_t ld_colsum,
+                                   int B, int H, int N, int E, int c, float softmax_scale, void* stream);
 
 /* Workspace bytes of chipmunk_mlp_tile_mean_preact (0 on bad arguments). */
 size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int F, int c);

@@ -33,6 +33,7 @@ _SIGNATURES = {
     "chipmunk_attn_dense_workspace_bytes": ([_c_int] * 3, _c_size),
     "chipmunk_attn_dense": ([_c_ptr] * 5 + [_c_i64] + [_c_int] * 5 + [_c_f32, _c_ptr, _c_size, _c_ptr],
                             ctypes.c_int32),
+    "chipmunk_attn_colsum_stale": ([_c_ptr] * 5 + [_c_i64] + [_c_int] * 5 + [_c_f32, _c_ptr], ctypes.c_int32),
     "chipmunk_mlp_tile_mean_workspace_bytes": ([_c_int] * 5, _c_size),
     "chipmunk_mlp_tile_mean_preact": ([_c_ptr] * 3 + [_c_int] * 5 + [_c_ptr, _c_size, _c_ptr], ctypes.c_int32),
     "chipmunk_mlp_workspace_bytes": ([_c_int] * 6, _c_size),
@@ -159,6 +160,22 @@ def attn_dense(q, k, v, out, colsum, c, softmax_scale, ws=None):
                                       _ptr(colsum, torch.float32, "colsum"), ld, B, H, N, E, c,
                                       float(softmax_scale), _ptr(ws, torch.uint8, "ws"),
                                       0 if ws is None else ws.numel(), _stream()), "chipmunk_attn_dense")
+
+
+def attn_dense_row_stats(ws, B, H, N):
+    """Views of the row statistics (m, l), fp32 [B,H,N] each, that attn_dense with column sums left in ws."""
+    stats = ws[: 2 * B * H * N * 4].view(torch.float32)
+    return stats[: B * H * N].view(B, H, N), stats[B * H * N:].view(B, H, N)
+
+
+def attn_colsum_stale(q, k, prev_m, prev_l, colsum, c, softmax_scale):
+    """q,k: bf16 [B,H,N,E]; prev_m, prev_l: fp32 [B,H,N]; colsum: fp32 [B,H,NB,ld] (written)."""
+    B, H, N, E = q.shape
+    bf, f32 = torch.bfloat16, torch.float32
+    _check(load().chipmunk_attn_colsum_stale(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(prev_m, f32, "prev_m"),
+                                             _ptr(prev_l, f32, "prev_l"), _ptr(colsum, f32, "colsum"),
+                                             colsum.shape[-1], B, H, N, E, c, float(softmax_scale), _stream()),
+           "chipmunk_attn_colsum_stale")
 
 
 def mlp_tile_mean_workspace_bytes(B, N, D, F, c):

@@ -27,8 +27,9 @@ struct AttnParams {
     uint16_t* out;
     const int32_t* idx;
     const int32_t* counts;
-    float* row_m2;  // optional [B,H,N]: reference max used per row, in log2 units
-    float* row_l;   // optional [B,H,N]: softmax denominator relative to row_m2
+    float* row_m;   // optional [B,H,N]: the reference the row's exponentials were taken against, in units of the
+                    // scaled scores (natural logarithm); within 2^8 of the row maximum, not necessarily equal to it
+    float* row_l;   // optional [B,H,N]: sum_j exp(score_j - row_m)
     int N, NB, c, k_stride;
     float sl2;      // softmax_scale * log2(e)
     float o_scale;
@@ -337,8 +338,8 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         float f = p.o_scale / ltot;
         int qrow = (w * NQB + qb) * 16 + l16;
         if (qrow < rows_valid) {
-            if (p.row_m2 && g == 0) {
-                p.row_m2[bh * p.N + row0 + qrow] = st.m2[qb];
+            if (p.row_m && g == 0) {
+                p.row_m[bh * p.N + row0 + qrow] = st.m2[qb] * 0.6931471805599453f;
                 p.row_l[bh * p.N + row0 + qrow] = ltot;
             }
 #pragma unroll
@@ -356,16 +357,17 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     }
 }
 
-// Exact column sums of the attention probabilities (Sec. 3.3.1, the tensor D):
-//   D[b,h,i,j] = sum over the rows q of chunk i of exp2(s_qj*sl2 - m2_q) / l_q
-// with (m2_q, l_q) from the dense attention pass.  Scores are produced as
+// Column sums of the attention probabilities (Sec. 3.3.1, the tensor D; Alg. 4):
+//   D[b,h,i,j] = sum over the rows q of chunk i of exp(scale*s_qj - m_q) / l_q
+// with (m_q, l_q) either from the dense attention pass of the same step (exact sums) or
+// carried over from an earlier step (the stale-normaliser approximation of App. B.2).  Scores are produced as
 // S = Q K^T (queries on the rows of the MFMA result), so that the sum over the
 // chunk's queries is a sum over a lane's registers, the wave's four 16-lane
 // rows and the workgroup's four waves.
 struct ColsumParams {
     const uint16_t* q;
     const uint16_t* k;
-    const float* row_m2;
+    const float* row_m;
     const float* row_l;
     float* colsum;
     int64_t ld;
@@ -410,7 +412,7 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
         for (int r = 0; r < 4; r++) {  // the MFMA result holds query 4g+r of the block in register r
             int qr = (w * NQB + qb) * 16 + 4 * g + r;
             bool ok = qr < rows_valid;
-            m2v[qb][r] = ok ? p.row_m2[bh * p.N + row0 + qr] : 0.f;
+            m2v[qb][r] = ok ? p.row_m[bh * p.N + row0 + qr] * 1.4426950408889634f : 0.f;
             il[qb][r] = ok ? 1.f / p.row_l[bh * p.N + row0 + qr] : 0.f;
         }
     }
@@ -498,6 +500,15 @@ static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_
     return launch_attn_variant<64, 2, 4>(p, units, s);
 }
 
+static int32_t launch_colsum(const ColsumParams& cp, int E, int64_t units, hipStream_t s) {
+    dim3 grid((unsigned)units), block(256);
+    if (E == 128 && cp.c == 192) hipLaunchKernelGGL((attn_colsum_kernel<128, 3>), grid, block, 0, s, cp);
+    else if (E == 128 && cp.c == 128) hipLaunchKernelGGL((attn_colsum_kernel<128, 2>), grid, block, 0, s, cp);
+    else if (E == 64 && cp.c == 192) hipLaunchKernelGGL((attn_colsum_kernel<64, 3>), grid, block, 0, s, cp);
+    else hipLaunchKernelGGL((attn_colsum_kernel<64, 2>), grid, block, 0, s, cp);
+    return launch_status();
+}
+
 }  // namespace chipmunk
 
 using namespace chipmunk;
@@ -522,7 +533,7 @@ extern "C" int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t*
     if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
     AttnParams p;
     p.q = q; p.k = k; p.v = v; p.base = base; p.out = out; p.idx = idx; p.counts = counts;
-    p.row_m2 = nullptr; p.row_l = nullptr;
+    p.row_m = nullptr; p.row_l = nullptr;
     p.N = N; p.NB = NB; p.c = c; p.k_stride = k_stride;
     p.sl2 = softmax_scale * 1.4426950408889634f;
     p.o_scale = o_scale;
@@ -553,7 +564,7 @@ extern "C" int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, con
     hipStream_t s = (hipStream_t)stream;
     AttnParams p;
     p.q = q; p.k = k; p.v = v; p.base = nullptr; p.out = out; p.idx = nullptr; p.counts = nullptr;
-    p.row_m2 = colsum ? (float*)ws : nullptr;
+    p.row_m = colsum ? (float*)ws : nullptr;
     p.row_l = colsum ? (float*)ws + (int64_t)B * H * N : nullptr;
     p.N = N; p.NB = NB; p.c = c; p.k_stride = 0;
     p.sl2 = softmax_scale * 1.4426950408889634f;
@@ -561,12 +572,27 @@ extern "C" int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, con
     int32_t st = launch_attn(p, E, units, s);
     if (st != CHIPMUNK_OK || !colsum) return st;
     ColsumParams cp;
-    cp.q = q; cp.k = k; cp.row_m2 = p.row_m2; cp.row_l = p.row_l; cp.colsum = colsum; cp.ld = ld_colsum;
+    cp.q = q; cp.k = k; cp.row_m = p.row_m; cp.row_l = p.row_l; cp.colsum = colsum; cp.ld = ld_colsum;
     cp.N = N; cp.NB = NB; cp.c = c; cp.sl2 = p.sl2;
-    dim3 grid((unsigned)units), block(256);
-    if (E == 128 && c == 192) hipLaunchKernelGGL((attn_colsum_kernel<128, 3>), grid, block, 0, s, cp);
-    else if (E == 128 && c == 128) hipLaunchKernelGGL((attn_colsum_kernel<128, 2>), grid, block, 0, s, cp);
-    else if (E == 64 && c == 192) hipLaunchKernelGGL((attn_colsum_kernel<64, 3>), grid, block, 0, s, cp);
-    else hipLaunchKernelGGL((attn_colsum_kernel<64, 2>), grid, block, 0, s, cp);
-    return launch_status();
+    return launch_colsum(cp, E, units, s);
+}
+
+extern "C" int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t* k, const float* prev_m,
+                                              const float* prev_l, float* colsum, int64_t ld_colsum, int B, int H,
+                                              int N, int E, int c, float softmax_scale, void* stream) {
+    if (!q || !k || !prev_m || !prev_l || !colsum) return CHIPMUNK_ERR_NULL;
+    if (B < 1 || H < 1 || N < 1 || ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
+    if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return CHIPMUNK_ERR_SHAPE;
+    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(colsum) || (ld_colsum % 4) != 0 ||
+        (reinterpret_cast<uintptr_t>(prev_m) & 3u) || (reinterpret_cast<uintptr_t>(prev_l) & 3u))
+        return CHIPMUNK_ERR_ALIGN;
+    int NB = (N + c - 1) / c;
+    int64_t units = (int64_t)B * H * NB;
+    if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
+    ColsumParams cp;
+    cp.q = q; cp.k = k; cp.row_m = prev_m; cp.row_l = prev_l; cp.colsum = colsum; cp.ld = ld_colsum;
+    cp.N = N; cp.NB = NB; cp.c = c; cp.sl2 = softmax_scale * 1.4426950408889634f;
+    return launch_colsum(cp, E, units, (hipStream_t)stream);
 }

@@ -233,6 +233,46 @@ def test_attn_dense_with_colsum_parity(cm, oracle, B, H, N, E, c):
     assert np.allclose(Dg.sum(-1), rows[None, None], rtol=2e-3)     # each row of P sums to one
 
 
+@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (2, 2, 700, 128, 192)])
+def test_attn_colsum_with_stale_normalisers_parity(cm, oracle, B, H, N, E, c):
+    """Alg. 4: the dense pass of one step leaves (m, l); the next step's column sums are taken against them."""
+    (q1, k1, v1), (q2, k2, _), _ = si.attn_steps(B, H, N, E, 7, DEV)
+    scale = 1.0 / math.sqrt(E)
+    NB = -(-N // c)
+    ld = -(-N // 4) * 4
+    out = torch.empty_like(q1)
+    D1 = torch.empty((B, H, NB, ld), dtype=torch.float32, device=DEV)
+    ws = _u8(cm.attn_dense_workspace_bytes(B, H, N))
+    cm.attn_dense(q1, k1, v1, out, D1, c, scale, ws)
+    m, l = cm.attn_dense_row_stats(ws, B, H, N)
+    m, l = m.clone(), l.clone()
+    # the statistics are a valid (reference, sum) pair: m + log l is the row's log-sum-exp, whatever reference m is
+    m_ref, l_ref = oracle.attn_row_stats(si.np_f32(q1), si.np_f32(k1), scale)
+    lse = m.cpu().numpy().astype(np.float64) + np.log(l.cpu().numpy().astype(np.float64))
+    assert np.abs(lse - (m_ref + np.log(l_ref))).max() <= 2e-3
+    assert (m.cpu().numpy() <= m_ref + 1e-3).all()        # a reference no larger than the row maximum ...
+    assert (m.cpu().numpy() >= m_ref - 8 * math.log(2.0) - 1e-3).all()   # ... and within 2^8 of it
+    # same step, same statistics: the exact column sums again
+    D_same = torch.full((B, H, NB, ld), -1.0, dtype=torch.float32, device=DEV)
+    cm.attn_colsum_stale(q1, k1, m, l, D_same, c, scale)
+    assert rel_err(D_same.cpu().numpy()[..., :N], D1.cpu().numpy()[..., :N].astype(np.float64)) <= 1e-4
+    # next step against the stale statistics
+    D2 = torch.full((B, H, NB, ld), -1.0, dtype=torch.float32, device=DEV)
+    cm.attn_colsum_stale(q2, k2, m, l, D2, c, scale)
+    ref = oracle.attn_colsum_stale(si.np_f32(q2), si.np_f32(k2), m.cpu().numpy().astype(np.float64),
+                                   l.cpu().numpy().astype(np.float64), c, scale)
+    got = D2.cpu().numpy()
+    assert rel_err(got[..., :N].astype(np.float64), ref) <= REL_TOL
+    assert (got[..., N:] == -1.0).all()                   # padding columns are not written
+    # and the selection it feeds (Alg. 4 -> top-k) is almost the one the exact column sums give
+    exact = oracle.attn_dense(si.np_f32(q2), si.np_f32(k2), si.np_f32(v1), c, scale, want_colsum=True)[1]
+    kk = max(8, N // 8)
+    top_stale = np.argsort(-got[..., :N], axis=-1)[..., :kk]
+    top_exact = np.argsort(-exact, axis=-1)[..., :kk]
+    overlap = np.mean([len(set(a) & set(b)) / kk for a, b in zip(top_stale.reshape(-1, kk), top_exact.reshape(-1, kk))])
+    assert overlap >= 0.9      # the approximation App. B.2 relies on: stale normalisers barely move the top-k set
+
+
 def _check_sampled_attn_units(cm, oracle, name, n_units, sparse_k):
     cfg = si.CONFIGS[name]
     B, H, E, c = cfg["B"], cfg["H"], cfg["E"], cfg["c"]

@@ -75,3 +75,8 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     d = lib.chipmunk_attn_dense
     assert d(a, a, a, a, a, 128, 1, 1, 128, 128, 192, 0.1, None, 0, None) == -5        # colsum needs ws
     assert d(a, a, a, a, a, 100, 1, 1, 128, 128, 192, 0.1, a, 1 << 20, None) == -2     # ld_colsum < N
+    cs = lib.chipmunk_attn_colsum_stale
+    assert cs(a, a, None, a, a, 128, 1, 1, 128, 128, 192, 0.1, None) == -1             # normalisers are required
+    assert cs(a, a, a, a, a, 100, 1, 1, 128, 128, 192, 0.1, None) == -2                # ld_colsum < N
+    assert cs(a, a, a, a, a, 128, 1, 1, 128, 96, 192, 0.1, None) == -4                 # E
+    assert cs(a, a, P(0x1002), a, a, 128, 1, 1, 128, 128, 192, 0.1, None) == -3        # fp32 alignment
