@@ -315,6 +315,42 @@ def stack_bench(cm, args, steps, warmup, dev):
     print(json.dumps(line))
 
 
+def ceilings_bench(dev):
+    """What the device sustains for bare bf16 MFMA streams (alone, and alternating with fp32 vector work as a
+    softmax between two GEMMs does) and for streaming reads and copies: context for the roofline fractions."""
+    from paper_2506_03275_amd import ceilings as cl
+    sink = torch.zeros(1 << 20, dtype=torch.float32, device=dev)
+    out = {"mfma_bf16_tflops": {}, "unit_note": "valu = fp32 FMAs per 393216 flop of MFMAs, in a phase of their own; "
+           "waves = waves per SIMD"}
+
+    def timed(fn, reps=3):
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return best
+
+    iters = 60000                                    # 20-40 ms per launch: long enough for the clocks to settle
+    for shape in (16, 32):
+        for waves in (1, 2):
+            for valu in (0, 64, 128):
+                ms = timed(lambda: cl.mfma_bf16(shape, waves, valu, iters // waves, sink))
+                name = f"{shape}x{shape}x{512 // shape}_waves{waves}_valu{valu}"
+                out["mfma_bf16_tflops"][name] = round(cl.mfma_flops(waves, iters // waves) / (ms * 1e-3) / 1e12, 1)
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
+    dst = torch.empty_like(src)
+    nbytes = src.numel() * 4
+    out["read_GBps"] = round(nbytes / (timed(lambda: cl.read(src, sink), 5) * 1e-3) / 1e9, 1)
+    out["copy_GBps_read_plus_write"] = round(2 * nbytes / (timed(lambda: cl.copy(src, dst), 5) * 1e-3) / 1e9, 1)
+    assert torch.equal(dst[:4096], src[:4096]) and torch.equal(dst[-4096:], src[-4096:])
+    print(json.dumps({"ceilings": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -329,6 +365,8 @@ def main():
     ap.add_argument("--index-structures", action="store_true",
                     help="also time the attention kernel alone on two other index structures of the same size: "
                          "columns drawn uniformly per chunk, and whole blocks of 128 consecutive columns")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="print what the device sustains for bare MFMA streams and streaming reads/copies, and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch a plain elementwise copy of 256 MiB (untimed), the known-size kernel that "
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -348,6 +386,9 @@ def main():
     cm.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.ceilings:
+        ceilings_bench(dev)
+        return
     if args.workload == "stack":
         stack_bench(cm, args, steps, warmup, dev)
         return

@@ -1,4 +1,5 @@
-"""Builds the HIP kernels and the C-ABI library (libchipmunk_hip.so) for gfx950, in-tree."""
+"""Builds the HIP kernels and the C-ABI library (libchipmunk_hip.so) for gfx950, in-tree, and beside it the
+device-ceiling probes that bench.py --ceilings times (libchipmunk_ceilings.so)."""
 import glob
 import os
 import subprocess
@@ -7,6 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libchipmunk_hip.so")
+PROBE_SRC = os.path.join(HERE, "probe", "ceilings.hip")
+PROBE_LIB = os.path.join(HERE, "libchipmunk_ceilings.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-honor-nans",
@@ -54,6 +57,11 @@ def build(verbose=False):
     subprocess.run(cmd, check=True)
     for o in objs:
         os.remove(o)
+    probe = subprocess.run([hipcc] + HIPCC_FLAGS + [PROBE_SRC, "-o", PROBE_LIB], stdout=subprocess.PIPE,
+                           stderr=subprocess.STDOUT, text=True)
+    if probe.returncode != 0:
+        sys.stderr.write(probe.stdout)
+        raise RuntimeError("hipcc failed on the ceiling probes")
     return LIB
 
 
