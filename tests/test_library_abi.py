@@ -80,3 +80,22 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert cs(a, a, a, a, a, 100, 1, 1, 128, 128, 192, 0.1, None) == -2                # ld_colsum < N
     assert cs(a, a, a, a, a, 128, 1, 1, 128, 96, 192, 0.1, None) == -4                 # E
     assert cs(a, a, P(0x1002), a, a, 128, 1, 1, 128, 128, 192, 0.1, None) == -3        # fp32 alignment
+
+
+def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
+    from paper_2506_03275_amd import ceilings
+    lib = ceilings.load()
+    text = open(os.path.join(ROOT, "paper_2506_03275_amd", "probe", "ceilings.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(chipmunk_probe_[a-z0-9_]+)\s*\(", text)))
+    assert len(declared) == 4
+    for name in declared:
+        assert hasattr(lib, name)
+    P = ctypes.c_void_p
+    a = P(0x1000)
+    assert lib.chipmunk_probe_mfma_flops(3, 10) == 0.0
+    assert lib.chipmunk_probe_mfma_bf16(16, 1, 0, 10, None, None) == -1
+    assert lib.chipmunk_probe_mfma_bf16(24, 1, 0, 10, a, None) == -1      # shape
+    assert lib.chipmunk_probe_mfma_bf16(32, 1, 32, 10, a, None) == -1     # valu_ops
+    assert lib.chipmunk_probe_read(a, 24, a, None) == -1                  # bytes % 16
+    assert lib.chipmunk_probe_copy(a, P(0x2008), 64, None) == -1          # alignment
