@@ -57,7 +57,8 @@ struct AttnState {
     f32x4 O[E / 16][NQB];
     f32x4 L[NQB];     // softmax denominator, accumulated by the MFMA against a row of ones
     bf16x8 Q[E / 32][NQB];
-    float m2[NQB];    // running reference max, in log2 units (score * sl2)
+    f32x4 negm[NQB];  // -m in all four registers: the C operand that starts every score accumulation
+    float m[NQB];     // running reference max, in units of the raw scores <q,k>
 };
 
 // The work on one tile of 32 selected key rows is split in three pieces so that
@@ -65,15 +66,13 @@ struct AttnState {
 // next to the exponentials of tile t (VALU), and the max bookkeeping of tile t+1
 // (VALU) next to the P.V products of tile t (MFMA).
 
-// S^T = K Q^T for one tile; rows at or beyond `count` are set to -inf when MASK.
+// S^T = K Q^T - m for one tile: raw scores relative to the reference max (the MFMA adds -m for free where a
+// separate subtraction would cost one vector instruction per score); rows at or beyond `count` are set to -inf
+// when MASK.
 template <int E, int NQB, bool MASK>
 __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<E, NQB>& st, const uint8_t* sK,
                                             int koff, int kv0, int count, int g) {
     constexpr int ROWB = E * 2;
-#pragma unroll
-    for (int u = 0; u < 2; u++)
-#pragma unroll
-        for (int qb = 0; qb < NQB; qb++) S[u][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int es = 0; es < E / 32; es++) {
 #pragma unroll
@@ -81,7 +80,7 @@ __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<
             bf16x8 kop = *reinterpret_cast<const bf16x8*>(sK + u * 16 * ROWB + (koff ^ (64 * es)));
 #pragma unroll
             for (int qb = 0; qb < NQB; qb++)
-                S[u][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, st.Q[es][qb], S[u][qb], 0, 0, 0);
+                S[u][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, st.Q[es][qb], es == 0 ? st.negm[qb] : S[u][qb], 0, 0, 0);
         }
     }
     if (MASK) {
@@ -97,36 +96,45 @@ __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<
     }
 }
 
-// Raise the reference max where this tile's scores exceed it by more than the
-// slack; O and the denominator are rescaled (rare after the first tiles).  The
-// common case costs a lane only the max over its own 8 scores per query block:
-// the reduction over the four lanes that share a query runs when some lane of
-// the wave has seen an excess.
+// Raise the reference max where this tile's relative scores exceed the slack
+// (2^8 in probability, given here in raw score units); O, the denominator and the
+// tile's relative scores are rescaled (rare after the first tiles).  The common
+// case costs a lane only the max over its own 8 scores per query block: the reduction over the four lanes that share a query runs when some
+// lane of the wave has seen an excess.  The first tile of a unit sets the
+// reference to the tile's row maximum, whatever its sign.
 template <int E, int NQB>
-__device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB], float sl2) {
+__device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, f32x4 (&S)[2][NQB], bool first, float sl2,
+                                                float slack) {
     float mx[NQB];
-    bool need = false;
+    bool need = first;
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
-        float a = fmaxf(fmaxf(S[0][qb][0], S[0][qb][1]), fmaxf(S[0][qb][2], S[0][qb][3]));
-        float b = fmaxf(fmaxf(S[1][qb][0], S[1][qb][1]), fmaxf(S[1][qb][2], S[1][qb][3]));
-        mx[qb] = fmaxf(a, b) * sl2;
-        need |= mx[qb] > st.m2[qb] + kRescaleSlack;
+        float a = fmaxf(fmaxf(S[0][qb][0], S[0][qb][1]), S[0][qb][2]);
+        float b = fmaxf(fmaxf(a, S[0][qb][3]), S[1][qb][0]);
+        float c = fmaxf(fmaxf(b, S[1][qb][1]), S[1][qb][2]);
+        mx[qb] = fmaxf(c, S[1][qb][3]);
+        need |= mx[qb] > slack;
     }
     if (__builtin_amdgcn_ballot_w64(need) != 0) {
 #pragma unroll
         for (int qb = 0; qb < NQB; qb++) {
-            float mnew = fmaxf(st.m2[qb], rows4_max(mx[qb]));
-            float alpha = __builtin_amdgcn_exp2f(st.m2[qb] - mnew);
-            st.m2[qb] = mnew;
+            float d = rows4_max(mx[qb]);             // the tile's row maximum relative to the reference
+            float up = first ? d : fmaxf(d, 0.f);    // the reference only rises, except when it is first set
+            float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-up * sl2);   // O and L are still zero on the first tile
+            st.m[qb] += up;
+            st.negm[qb] = f32x4{-st.m[qb], -st.m[qb], -st.m[qb], -st.m[qb]};
             st.L[qb] *= alpha;
 #pragma unroll
             for (int eb = 0; eb < E / 16; eb++) st.O[eb][qb] *= alpha;
+#pragma unroll
+            for (int u = 0; u < 2; u++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) S[u][qb][r] -= up;
         }
     }
 }
 
-// P = exp2(S*sl2 - m2) in bf16, the denominator, and O^T += V^T P^T.
+// P = exp2(S*sl2) in bf16, the denominator, and O^T += V^T P^T.
 // The transposing V reads do not depend on the probabilities: the first kVPrefetch
 // operands are requested before the exponentials, the rest kVPrefetch steps ahead
 // of the MFMAs that consume them, so LDS latency stays off the MFMA chain.
@@ -153,7 +161,7 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
         for (int u = 0; u < 2; u++)
 #pragma unroll
             for (int r = 0; r < 4; r++)
-                pv[u * 4 + r] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[u][qb][r], sl2, -st.m2[qb]));
+                pv[u * 4 + r] = __builtin_amdgcn_exp2f(S[u][qb][r] * sl2);
         u32x4 packed;
 #pragma unroll
         for (int t = 0; t < 4; t++) packed[t] = pack_bf16x2(pv[2 * t], pv[2 * t + 1]);
@@ -232,7 +240,8 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     AttnState<E, NQB> st;
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
-        st.m2[qb] = -INFINITY;
+        st.m[qb] = 0.f;  // replaced by the first tile's row maximum
+        st.negm[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.L[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int eb = 0; eb < E / 16; eb++) st.O[eb][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -246,6 +255,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         }
     }
     const bool wave_active = w * NQB * 16 < rows_valid;
+    const float slack = kRescaleSlack / p.sl2;
     const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 
@@ -323,7 +333,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
                         attn_scores<E, NQB, false>(S, st, cK, koff, (t + s) * kTileRows, count, g);
                     else
                         attn_scores<E, NQB, true>(S, st, cK, koff, (t + s) * kTileRows, count, g);
-                    attn_update_max<E, NQB>(st, S, p.sl2);
+                    attn_update_max<E, NQB>(st, S, t + s == 0, p.sl2, slack);
                     attn_weights_and_pv<E, NQB>(st, S, cK + TILE, voff, p.sl2, ones);
                 }
             }
@@ -339,7 +349,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         int qrow = (w * NQB + qb) * 16 + l16;
         if (qrow < rows_valid) {
             if (p.row_m && g == 0) {
-                p.row_m[bh * p.N + row0 + qrow] = st.m2[qb] * 0.6931471805599453f;
+                p.row_m[bh * p.N + row0 + qrow] = st.m[qb] * (p.sl2 * 0.6931471805599453f);
                 p.row_l[bh * p.N + row0 + qrow] = ltot;
             }
 #pragma unroll
