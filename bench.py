@@ -365,6 +365,8 @@ def main():
     ap.add_argument("--index-structures", action="store_true",
                     help="also time the attention kernel alone on two other index structures of the same size: "
                          "columns drawn uniformly per chunk, and whole blocks of 128 consecutive columns")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step captured as one HIP graph (reported beside the eager numbers)")
     ap.add_argument("--ceilings", action="store_true",
                     help="print what the device sustains for bare MFMA streams and streaming reads/copies, and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -425,9 +427,28 @@ def main():
                 "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.workload) if args.attn_keep is None else None,
                 "launch_ms": attn_ms, "algorithmic_flops_per_launch": fl_attn}
 
+    graph_extra = None
+    if args.graph:
+        # The same step as one HIP graph: no launch gaps and no per-stage events between the kernels.
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            sparse_step(cm, st)
+        for _ in range(max(warmup, 1)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / steps
+        assert torch.equal(st["x"], st["x_expect"]), "voxel reorder did not restore the token order (graph replay)"
+        graph_extra = {"ms_per_step": g_ms, "useful_tflops": (fl_attn + fl_mlp) / (g_ms * 1e-3) / 1e12}
+
     extra = {"stage_ms": stages,
              "attn_useful_tflops": achieved,
              "mlp_useful_tflops": fl_mlp / (stages["mlp_sparse_delta"] * 1e-3) / 1e12}
+    if graph_extra is not None:
+        extra["hip_graph"] = graph_extra
     if args.index_structures:
         R = st["B"] * st["H"] * st["NB"]
         kinds = {"topk_of_column_sums": (st["idx_a"], st["cnt_a"])}

@@ -93,3 +93,47 @@ def test_stack_overlap_equals_serial():
     for key in serial:
         for a, b in zip(serial[key], overlapped[key]):
             assert torch.equal(a, b), key
+
+
+def test_stack_sparse_step_as_hip_graph():
+    """The sparse step is kernel launches only (no allocation, no memset, no host wait), so it can be captured as one
+    HIP graph.  Every replay, with eager steps and synchronisations in between, must reproduce the eager result."""
+    import paper_2506_03275_amd as cm
+    from paper_2506_03275_amd import stack
+    cm.load()
+    cfg = si.CONFIGS["tiny"]
+    N = si.config_tokens(cfg)
+    k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
+    inputs = si.stack_inputs(cfg, 2, 3, 11, DEV)
+    blocks = [stack.Block(inp, cfg["c"], k_a, k_m) for inp in inputs]
+    stack.dense_step(blocks, 0)
+    torch.cuda.synchronize()
+    saved = [(blk.a_cache.clone(), blk.m_cache.clone()) for blk in blocks]
+
+    def restore():                      # the step merges into the MLP caches in place
+        for blk, (a, m) in zip(blocks, saved):
+            blk.a_cache.copy_(a)
+            blk.m_cache.copy_(m)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for blk in blocks for t in (blk.attn_out, blk.m_cache, blk.a_cache, blk.idx_m, blk.cnt_m)]
+
+    def same(a, b):
+        return all(torch.equal(x, y) for x, y in zip(a, b))
+
+    stack.sparse_step(blocks, 1)
+    eager = snapshot()
+    restore()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stack.sparse_step(blocks, 1)
+    for replay in range(3):
+        restore()
+        torch.cuda.synchronize()
+        graph.replay()
+        assert same(snapshot(), eager), f"replay {replay}"
+        restore()
+        stack.sparse_step(blocks, 1)    # eager work between the replays
+        assert same(snapshot(), eager), f"eager run after replay {replay}"
