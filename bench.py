@@ -342,6 +342,14 @@ def ceilings_bench(dev):
                 ms = timed(lambda: cl.mfma_bf16(shape, waves, valu, iters // waves, sink))
                 name = f"{shape}x{shape}x{512 // shape}_waves{waves}_valu{valu}"
                 out["mfma_bf16_tflops"][name] = round(cl.mfma_flops(waves, iters // waves) / (ms * 1e-3) / 1e12, 1)
+    out["mfma_slots_tflops"] = {}
+    for shape in (16, 32):
+        for waves in (1, 2):
+            for group in (0, 1):
+                it = 30000 // waves
+                ms = timed(lambda: cl.mfma_slots(shape, waves, group, it, sink))
+                name = f"{shape}x{shape}x{512 // shape}_waves{waves}_" + ("softmax_pair_per_32768_flop" if group else "alone")
+                out["mfma_slots_tflops"][name] = round(cl.mfma_slots_flops(waves, it) / (ms * 1e-3) / 1e12, 1)
     src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
     dst = torch.empty_like(src)
     nbytes = src.numel() * 4

@@ -66,6 +66,51 @@ __global__ __launch_bounds__(256) void mfma32_kernel(float* sink, int iters) {
     sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// One MFMA followed by the vector work of one pair of softmax probabilities (two multiply-subtracts, two
+// exponentials, one bf16 pack), every instruction pinned in place by inline assembly.  SHAPE 32: the group follows
+// every 32x32x16 MFMA; SHAPE 16: every second 16x16x32 MFMA (the same vector work per flop).  GROUP = false leaves
+// the MFMAs alone.
+template <int SHAPE, bool GROUP>
+__global__ __launch_bounds__(256) void mfma_slot_kernel(float* sink, int iters) {
+    bf16x8 a, b;
+    probe_operands(a, b);
+    f32x16 acc32[6];
+    f32x4 acc16[12];
+    for (int i = 0; i < 6; i++)
+        for (int r = 0; r < 16; r++) acc32[i][r] = 0.f;
+    for (int i = 0; i < 12; i++) acc16[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float v[8];
+    for (int i = 0; i < 8; i++) v[i] = threadIdx.x * 0.001f + i;
+    const float scale = 0.25f, ref = 3.f;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int s = 0; s < 24; s++) {
+            if (SHAPE == 32) {
+                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc32[s % 6]) : "v"(a), "v"(b));
+            } else {
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc16[(2 * s) % 12]) : "v"(a), "v"(b));
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc16[(2 * s + 1) % 12]) : "v"(a), "v"(b));
+            }
+            if (GROUP) {
+                float x0, x1;
+                uint32_t pk;
+                asm volatile("v_fma_f32 %0, %2, %4, -%5\n\tv_fma_f32 %1, %3, %4, -%5"
+                             : "=&v"(x0), "=&v"(x1)
+                             : "v"(v[s & 7]), "v"(v[(s + 3) & 7]), "s"(scale), "v"(ref));
+                asm volatile("s_nop 0\n\tv_exp_f32 %0, %0\n\tv_exp_f32 %1, %1" : "+v"(x0), "+v"(x1));
+                asm volatile("s_nop 0\n\tv_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(x0), "v"(x1));
+                v[s & 7] = __uint_as_float(pk & 0x3fffffffu);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float sum = 0.f;
+    for (int i = 0; i < 6; i++) sum += acc32[i][0] + acc32[i][7];
+    for (int i = 0; i < 12; i++) sum += acc16[i][0] + acc16[i][3];
+    for (int i = 0; i < 8; i++) sum += v[i];
+    sink[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
 __global__ __launch_bounds__(256) void read_kernel(const float4* __restrict__ x, size_t n4, float* sink) {
     constexpr int U = 8;
     const size_t stride = (size_t)gridDim.x * 256 * U;
@@ -133,6 +178,28 @@ extern "C" int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int va
         if (valu_ops == 0) hipLaunchKernelGGL(mfma32_kernel<0>, grid, block, 0, s, sink, iters);
         else if (valu_ops == 64) hipLaunchKernelGGL(mfma32_kernel<64>, grid, block, 0, s, sink, iters);
         else hipLaunchKernelGGL(mfma32_kernel<128>, grid, block, 0, s, sink, iters);
+    }
+    return status();
+}
+
+extern "C" double chipmunk_probe_mfma_slots_flops(int blocks_per_cu, int iters) {
+    if ((blocks_per_cu != 1 && blocks_per_cu != 2) || iters < 1) return 0.0;
+    return 24.0 * 32 * 32 * 16 * 2 * 4.0 * (double)compute_units() * blocks_per_cu * iters;
+}
+
+extern "C" int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int with_vector_group, int iters, float* sink,
+                                             void* stream) {
+    if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2) || (shape != 16 && shape != 32)) return -1;
+    const int cus = compute_units();
+    if (cus < 1) return -6;
+    dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
+    hipStream_t s = (hipStream_t)stream;
+    if (shape == 32) {
+        if (with_vector_group) hipLaunchKernelGGL((mfma_slot_kernel<32, true>), grid, block, 0, s, sink, iters);
+        else hipLaunchKernelGGL((mfma_slot_kernel<32, false>), grid, block, 0, s, sink, iters);
+    } else {
+        if (with_vector_group) hipLaunchKernelGGL((mfma_slot_kernel<16, true>), grid, block, 0, s, sink, iters);
+        else hipLaunchKernelGGL((mfma_slot_kernel<16, false>), grid, block, 0, s, sink, iters);
     }
     return status();
 }
