@@ -4,9 +4,12 @@
 // One workgroup (4 waves) owns one chunk of c query rows of one (batch, head).
 // It walks the chunk's selected key columns in tiles of 32: the K and V rows
 // named by the index list are gathered from global memory straight into LDS
-// (16-byte asynchronous loads, one K or V row = E*2 contiguous bytes) through
-// a ring of five tile buffers, so that three to four tiles are in flight while
-// one is consumed by bf16 MFMA 16x16x32 with an fp32 online softmax.
+// (16-byte asynchronous loads, one K or V row = E*2 contiguous bytes), two
+// tiles per workgroup barrier and double buffered: the two tiles of the next
+// step are in flight while the two of this step are consumed by bf16 MFMA
+// 16x16x32 with an fp32 online softmax.  Two workgroups share a compute unit
+// (two waves per SIMD): a wave hides nothing behind its own MFMAs, the other
+// wave's vector and LDS instructions are what runs in their shadow.
 //
 // Register-level layout.  Scores are produced transposed, S^T = K Q^T, so a
 // lane holds, for ONE query (lane % 16), the scores of 4 key rows per 16-row
