@@ -314,6 +314,39 @@ def test_attn_wan_shape_sampled_units(cm, oracle):
     _check_sampled_attn_units(cm, oracle, "wan", 6, 5292)
 
 
+def test_attn_dense_and_column_sums_hunyuan_shape_sampled_units(cm, oracle):
+    """The dense step at the full HunyuanVideo shape (the launch bench.py uses to fill the caches): output, exact
+    column sums and the stale-normaliser column sums of sampled chunks against the oracle."""
+    cfg = si.CONFIGS["hunyuan"]
+    B, H, E, c = cfg["B"], cfg["H"], cfg["E"], cfg["c"]
+    N = si.config_tokens(cfg)
+    (q1, k1, v1), (q2, k2, _), _ = si.attn_steps(B, H, N, E, 3, DEV)
+    del v1
+    v = si.randn_bf16((B, H, N, E), si.generator(4, DEV))
+    NB = -(-N // c)
+    ld = -(-N // 4) * 4
+    scale = 1.0 / math.sqrt(E)
+    out = torch.empty_like(q1)
+    D = torch.empty((B, H, NB, ld), dtype=torch.float32, device=DEV)
+    ws = _u8(cm.attn_dense_workspace_bytes(B, H, N))
+    cm.attn_dense(q1, k1, v, out, D, c, scale, ws)
+    m, l = cm.attn_dense_row_stats(ws, B, H, N)
+    D2 = torch.empty_like(D)
+    cm.attn_colsum_stale(q2, k2, m, l, D2, c, scale)
+    torch.cuda.synchronize()
+    for b, h, i in [(0, 0, 0), (B - 1, H - 1, NB - 1), (0, H // 2, NB // 3)]:
+        rows = slice(i * c, min(N, (i + 1) * c))
+        kn, vn = si.np_f32(k1[b:b + 1, h:h + 1]), si.np_f32(v[b:b + 1, h:h + 1])
+        ref, Dref = oracle.attn_dense(si.np_f32(q1[b:b + 1, h:h + 1, rows]), kn, vn, c, scale, want_colsum=True)
+        assert rel_err(si.np_f32(out[b:b + 1, h:h + 1, rows]), ref) <= REL_TOL, (b, h, i)
+        assert rel_err(D[b, h, i, :N].cpu().numpy().astype(np.float64), Dref[0, 0, 0]) <= REL_TOL, (b, h, i)
+        ms = m[b:b + 1, h:h + 1, rows].cpu().numpy().astype(np.float64)
+        ls = l[b:b + 1, h:h + 1, rows].cpu().numpy().astype(np.float64)
+        ref2 = oracle.attn_colsum_stale(si.np_f32(q2[b:b + 1, h:h + 1, rows]), si.np_f32(k2[b:b + 1, h:h + 1]), ms, ls, c,
+                                        scale)
+        assert rel_err(D2[b, h, i, :N].cpu().numpy().astype(np.float64), ref2[0, 0, 0]) <= REL_TOL, (b, h, i)
+
+
 # ---------------------------------------------------------------------- MLP ---
 
 def _mlp_tensors(B, N, D, F, seed):
