@@ -422,8 +422,9 @@ def test_mlp_sparse_delta_parity(cm, oracle, B, N, D, F, c, k, act):
         x2 = si.perturb_all(x2, si.generator(77 + step, DEV))
 
 
-def test_mlp_flux_shape_sampled_units(cm, oracle):
-    cfg = si.CONFIGS["flux"]
+@pytest.mark.parametrize("name,chunks", [("flux", (0, 7, -1)), ("hunyuan", (0, -1)), ("wan", (3, -1))])
+def test_mlp_full_shape_sampled_units(cm, oracle, name, chunks):
+    cfg = si.CONFIGS[name]
     B, D, F, c = cfg["B"], cfg["D"], cfg["F"], cfg["c"]
     N = si.config_tokens(cfg)
     k = si.kept(F, cfg["mlp_keep"])
@@ -441,7 +442,7 @@ def test_mlp_flux_shape_sampled_units(cm, oracle):
     cm.mlp_sparse_delta(x2, w1, b1, w2, idx, counts, a_cache, out, c, act, ws)
     torch.cuda.synchronize()
     w1n, b1n, w2n, b2n = si.np_f32(w1), si.np_f32(b1), si.np_f32(w2), si.np_f32(b2)
-    for i in (0, 7, NB - 1):                                          # sampled token chunks, each a B=1, N=c problem
+    for i in [ch % NB for ch in chunks]:                              # sampled token chunks, each a B=1, N=c problem
         rows = slice(i * c, min(N, (i + 1) * c))
         n = rows.stop - rows.start
         dref = oracle.mlp_dense(si.np_f32(x1[:, rows]), w1n, b1n, w2n, b2n, c, act, want_caches=False)
