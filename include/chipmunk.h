@@ -14,7 +14,10 @@
  *   - Return value: CHIPMUNK_OK, or a negative code; on any error nothing was
  *     launched.  chipmunk_status_string() gives a text for a code.
  *   - Index contents (range, duplicates) are preconditions that are not
- *     checked: every idx entry below its row's count must lie in [0, C).
+ *     reported: every idx entry below its row's count must lie in [0, C) and
+ *     every count in [0, k_stride].  The kernels clamp both into range, so a
+ *     bad entry gives a wrong result for its chunk, not an access outside the
+ *     tensors.
  *   - "chunk" = c consecutive tokens that share one set of selected columns
  *     (the [C,1] column sparsity of Sec. 3.2.1); the last chunk of a sequence
  *     may hold fewer than c tokens.  NB = ceil(N / c).

@@ -222,7 +222,9 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const int chunk = (int)(unit % p.NB);
     const int row0 = chunk * p.c;
     const int rows_valid = min(p.c, p.N - row0);
-    const int count = __builtin_amdgcn_readfirstlane(p.counts ? p.counts[unit] : p.N);
+    // Contents of counts and idx are the caller's precondition; they are clamped all the same so that a bad
+    // entry reads a wrong row instead of leaving the tensors.
+    const int count = __builtin_amdgcn_readfirstlane(p.counts ? min(p.counts[unit], p.k_stride) : p.N);
 
     const int64_t head_off = bh * (int64_t)p.N * E;
     const uint16_t* qh = p.q + head_off;
@@ -300,7 +302,8 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             for (int i = 0; i < NI; i++) {
                 int row = (i * NWAVES + w) * RPI + sel;
                 // byte offset of this lane's chunk inside the head's K (and V) matrix
-                uint32_t goff = (uint32_t)colv[s][i] * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
+                // clamped here, where the load has landed anyway, not where it is issued
+                uint32_t goff = (uint32_t)min(max(colv[s][i], 0), p.N - 1) * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
                 uint32_t dst = lds0 + (uint32_t)((half * kTilesPerStep + s) * STAGE + i * NWAVES * 1024);
                 load_global_to_lds_16B(kh, goff, dst);
                 load_global_to_lds_16B(vh, goff, dst + TILE);

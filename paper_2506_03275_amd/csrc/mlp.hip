@@ -94,7 +94,8 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     const int b = unit / p.NB, chunk = unit % p.NB;
     const int row0 = chunk * BM;
     const int col0 = col_tile * kBN;
-    const int count = p.counts ? p.counts[unit] : p.F;
+    const int count = p.counts ? min(p.counts[unit], p.k_stride) : p.F;   // clamped like the indices below: a bad
+                                                                          // entry must not leave the tensors
     if (col0 >= count && MODE != kSparseDelta) return;
     if (MODE == kSparseDelta && col0 >= ((count + kBK - 1) / kBK) * kBK) return;  // nothing to compute or to zero
 
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     if (tid < kBN) {
         int s = col0 + tid;
         int last = max(count - 1, 0);
-        int f = p.idx ? p.idx[(int64_t)unit * p.k_stride + min(s, last)] : min(s, last);
+        int f = p.idx ? min(max(p.idx[(int64_t)unit * p.k_stride + min(s, last)], 0), p.F - 1) : min(s, last);
         s_neuron[tid] = f;
     }
     __syncthreads();
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
     const int b = unit / p.NB, chunk = unit % p.NB;
     const int row0 = chunk * BM;
     const int d0 = col_tile * kBN;
-    const int count = p.counts ? p.counts[unit] : p.F;
+    const int count = p.counts ? min(p.counts[unit], p.k_stride) : p.F;
     if (count <= 0 && !p.dense) return;            // nothing selected: the cache stays as it is
     const int32_t* idxp = p.idx ? p.idx + (int64_t)unit * p.k_stride : nullptr;
     const int ktiles = (count + kBK - 1) / kBK;
@@ -352,7 +353,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
         for (int i = 0; i < NIA; i++) load_global_to_lds_16B(as, aoff_g[i], lds0 + stage * STAGE + i * 4096);
 #pragma unroll
         for (int i = 0; i < NIW; i++)
-            load_global_to_lds_16B(w2b, (uint32_t)cols[i] * (uint32_t)(p.D * 2) + wchunk[i],
+            load_global_to_lds_16B(w2b, (uint32_t)min(max(cols[i], 0), p.F - 1) * (uint32_t)(p.D * 2) + wchunk[i],
                                    lds0 + stage * STAGE + AT + i * 4096);
     };
 
