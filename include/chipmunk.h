@@ -128,6 +128,23 @@ int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t* k, const f
                                    const float* prev_l, float* colsum, int64_t ld_colsum,
                                    int B, int H, int N, int E, int c, float softmax_scale, void* stream);
 
+/* Dense attention and the column sums with given normalisers in one pass (Alg. 4):
+ *   out = softmax(softmax_scale * q k^T) v            with this step's own normalisers,
+ *   colsum[b,h,i,j] = sum over the rows n of chunk i of
+ *                     exp(softmax_scale * <q[n],k[j]> - prev_m[n]) / prev_l[n]
+ * from the same score tiles (no second pass over q k^T and no workspace).
+ * new_m, new_l: [B,H,N] fp32 or both NULL; they receive this step's statistics
+ * in the form chipmunk_attn_dense leaves them, for the next step's prev_m,
+ * prev_l.  new_m == prev_m and new_l == prev_l (update in place) is allowed:
+ * the workgroup of a chunk reads the old values of its own rows, and only
+ * those, before it writes the new ones; any other overlap is not.  Other
+ * arguments as for chipmunk_attn_colsum_stale and chipmunk_attn_dense. */
+int32_t chipmunk_attn_dense_colsum_stale(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                                         uint16_t* out, const float* prev_m, const float* prev_l,
+                                         float* colsum, int64_t ld_colsum, float* new_m, float* new_l,
+                                         int B, int H, int N, int E, int c, float softmax_scale,
+                                         void* stream);
+
 /* Workspace bytes of chipmunk_mlp_tile_mean_preact (0 on bad arguments). */
 size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int F, int c);
 

@@ -34,6 +34,8 @@ _SIGNATURES = {
     "chipmunk_attn_dense": ([_c_ptr] * 5 + [_c_i64] + [_c_int] * 5 + [_c_f32, _c_ptr, _c_size, _c_ptr],
                             ctypes.c_int32),
     "chipmunk_attn_colsum_stale": ([_c_ptr] * 5 + [_c_i64] + [_c_int] * 5 + [_c_f32, _c_ptr], ctypes.c_int32),
+    "chipmunk_attn_dense_colsum_stale": ([_c_ptr] * 7 + [_c_i64] + [_c_ptr] * 2 + [_c_int] * 5 + [_c_f32, _c_ptr],
+                                         ctypes.c_int32),
     "chipmunk_mlp_tile_mean_workspace_bytes": ([_c_int] * 5, _c_size),
     "chipmunk_mlp_tile_mean_preact": ([_c_ptr] * 3 + [_c_int] * 5 + [_c_ptr, _c_size, _c_ptr], ctypes.c_int32),
     "chipmunk_mlp_workspace_bytes": ([_c_int] * 6, _c_size),
@@ -176,6 +178,19 @@ def attn_colsum_stale(q, k, prev_m, prev_l, colsum, c, softmax_scale):
                                              _ptr(prev_l, f32, "prev_l"), _ptr(colsum, f32, "colsum"),
                                              colsum.shape[-1], B, H, N, E, c, float(softmax_scale), _stream()),
            "chipmunk_attn_colsum_stale")
+
+
+def attn_dense_colsum_stale(q, k, v, out, prev_m, prev_l, colsum, c, softmax_scale, new_m=None, new_l=None):
+    """Alg. 4 in one kernel.  q,k,v,out: bf16 [B,H,N,E]; prev_m, prev_l, new_m, new_l: fp32 [B,H,N]; colsum: fp32
+    [B,H,NB,ld] (written)."""
+    B, H, N, E = q.shape
+    bf, f32 = torch.bfloat16, torch.float32
+    _check(load().chipmunk_attn_dense_colsum_stale(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(v, bf, "v"),
+                                                   _ptr(out, bf, "out"), _ptr(prev_m, f32, "prev_m"),
+                                                   _ptr(prev_l, f32, "prev_l"), _ptr(colsum, f32, "colsum"),
+                                                   colsum.shape[-1], _ptr(new_m, f32, "new_m"),
+                                                   _ptr(new_l, f32, "new_l"), B, H, N, E, c, float(softmax_scale),
+                                                   _stream()), "chipmunk_attn_dense_colsum_stale")
 
 
 def mlp_tile_mean_workspace_bytes(B, N, D, F, c):

@@ -36,6 +36,11 @@ struct AttnParams {
     int N, NB, c, k_stride;
     float sl2;      // softmax_scale * log2(e)
     float o_scale;
+    // fused column sums with given normalisers (Alg. 4): dense launches of the FUSED kernel only
+    const float* prev_m;   // [B,H,N], natural-log units like row_m
+    const float* prev_l;   // [B,H,N]
+    float* colsum;         // [B,H,NB,ld_colsum]
+    int64_t ld_colsum;
 };
 
 constexpr int kTileRows = 32;         // key rows per LDS tile = one step of the online softmax
@@ -143,9 +148,35 @@ __device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, f32x4 (&S
 // of the MFMAs that consume them, so LDS latency stays off the MFMA chain.
 constexpr int kVPrefetch = 3;
 
-template <int E, int NQB>
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {  // x of the lane that the DPP control CTRL names
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+
+// acc[4 u + r] is the lane's value for tile key row 16 u + 4 g + r.  Sums each of the eight over the 16 lanes of
+// the row (the wave's 16 queries of a block) and writes them to part[32] in tile key order.  Halving exchange:
+// at each step a lane keeps half of its values and hands the other half to a partner that keeps those, so 8 adds
+// stand in for 32.  Partners: lane ^ 15, ^ 7, ^ 3, ^ 1; the value a lane ends with is 4 bit3 + 2 bit2 + bit1.
+__device__ __forceinline__ void row16_sums_to_lds(const float (&acc)[8], float* part, int g, int l16) {
+    const bool b3 = l16 & 8, b2 = l16 & 4, b1 = l16 & 2;
+    float x[4], y[2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) x[i] = (b3 ? acc[i + 4] : acc[i]) + dpp_f32<0x140>(b3 ? acc[i] : acc[i + 4]);  // row_mirror
+#pragma unroll
+    for (int i = 0; i < 2; i++) y[i] = (b2 ? x[i + 2] : x[i]) + dpp_f32<0x141>(b2 ? x[i] : x[i + 2]);          // row_half_mirror
+    float z = (b1 ? y[1] : y[0]) + dpp_f32<0x1b>(b1 ? y[0] : y[1]);                                              // quad_perm 3,2,1,0
+    z += dpp_f32<0xb1>(z);                                                                                       // quad_perm 1,0,3,2
+    if (!(l16 & 1)) part[(l16 & 8 ? 16 : 0) + 4 * g + ((l16 >> 1) & 3)] = z;
+}
+
+// COLSUM (Alg. 4): also the tile's column sums with given normalisers.  The weight of (key, query) there is
+// exp2(score * sl2 - prev_m2) / prev_l = p * wq, with p the probability formed here against the running
+// reference st.m and wq = exp2(st.m * sl2 + off) per query, off = -prev_m2 - log2(prev_l) (-inf: no such query).
+template <int E, int NQB, bool COLSUM = false>
 __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB],
-                                                    const uint8_t* sV, int voff, float sl2, bf16x8 ones) {
+                                                    const uint8_t* sV, int voff, float sl2, bf16x8 ones,
+                                                    const float* off = nullptr, float* part = nullptr, int g = 0,
+                                                    int l16 = 0) {
     constexpr int ROWB = E * 2;
     constexpr int NEB = E / 16;
     typedef __attribute__((ext_vector_type(8))) short short8v;
@@ -157,6 +188,7 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * kVPrefetch, 0);  // the LDS reads lead the block
     bf16x8 pop[NQB];
+    float acc[8];
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
         float pv[8];
@@ -165,11 +197,18 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
 #pragma unroll
             for (int r = 0; r < 4; r++)
                 pv[u * 4 + r] = __builtin_amdgcn_exp2f(S[u][qb][r] * sl2);
+        if (COLSUM) {
+            // the cap keeps wq finite, so that a zero probability times it stays zero
+            const float wq = __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(st.m[qb], sl2, off[qb]), 126.f));
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[j] = qb == 0 ? pv[j] * wq : __builtin_fmaf(pv[j], wq, acc[j]);
+        }
         u32x4 packed;
 #pragma unroll
         for (int t = 0; t < 4; t++) packed[t] = pack_bf16x2(pv[2 * t], pv[2 * t + 1]);
         pop[qb] = __builtin_bit_cast(bf16x8, packed);
     }
+    if (COLSUM) row16_sums_to_lds(acc, part, g, l16);
     // denominator from the same bf16 probabilities that weight V
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++)
@@ -198,7 +237,8 @@ __device__ __forceinline__ void wait_vmem_at_most() {  // at most N vector-memor
 }
 
 // NWAVES waves per workgroup, each owning NQB blocks of 16 queries: c = 16 * NQB * NWAVES.
-template <int E, int NQB, int NWAVES>
+// FUSED (dense launches only: no index list): the column sums of Alg. 4 are formed from the same score tiles.
+template <int E, int NQB, int NWAVES, bool FUSED = false>
 __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_delta_kernel(AttnParams p) {
     constexpr int ROWB = E * 2;           // bytes per K/V row
     constexpr int CH = ROWB / 16;         // 16-byte chunks per row
@@ -209,6 +249,8 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     constexpr int STAGE = 2 * TILE;       // K tile then V tile
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];  // kStages * STAGE bytes
+    // FUSED: per-wave column sums of the two tiles of a step, double buffered over steps
+    __shared__ float s_part[FUSED ? 2 * NWAVES * kTilesPerStep * kTileRows : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -261,6 +303,30 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     }
     const bool wave_active = w * NQB * 16 < rows_valid;
     const float slack = kRescaleSlack / p.sl2;
+    // FUSED: -prev_m (log2 units) - log2(prev_l) of the lane's queries; -inf drops a query row that does not exist
+    float off[NQB];
+    if (FUSED) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; qb++) {
+            int qrow = (w * NQB + qb) * 16 + l16;
+            off[qb] = -INFINITY;
+            if (qrow < rows_valid) {
+                const int64_t at = bh * p.N + row0 + qrow;
+                off[qb] = -p.prev_m[at] * 1.4426950408889634f - __builtin_amdgcn_logf(p.prev_l[at]);
+            }
+        }
+    }
+    const int active_waves = min(NWAVES, (rows_valid + NQB * 16 - 1) / (NQB * 16));
+    float* colsum_row = FUSED ? p.colsum + unit * p.ld_colsum : nullptr;
+    auto flush_column_sums = [&](int tile0) {  // sums of tiles tile0, tile0+1: the waves' partial sums -> global
+        if (FUSED && tid < kTilesPerStep * kTileRows) {
+            const float* part = s_part + ((tile0 / kTilesPerStep) & 1) * (NWAVES * kTilesPerStep * kTileRows);
+            float v = 0.f;
+            for (int ww = 0; ww < active_waves; ww++) v += part[ww * (kTilesPerStep * kTileRows) + tid];
+            const int j = tile0 * kTileRows + tid;
+            if (j < p.N) colsum_row[j] = v;
+        }
+    };
     const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 
@@ -329,6 +395,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             gather(half ^ 1);
             load_cols(t + 2 * kTilesPerStep);
         }
+        if (FUSED && t > 0) flush_column_sums(t - kTilesPerStep);
         if (wave_active) {
 #pragma unroll
             for (int s = 0; s < kTilesPerStep; s++) {
@@ -340,11 +407,17 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
                     else
                         attn_scores<E, NQB, true>(S, st, cK, koff, (t + s) * kTileRows, count, g);
                     attn_update_max<E, NQB>(st, S, t + s == 0, p.sl2, slack);
-                    attn_weights_and_pv<E, NQB>(st, S, cK + TILE, voff, p.sl2, ones);
+                    attn_weights_and_pv<E, NQB, FUSED>(
+                        st, S, cK + TILE, voff, p.sl2, ones, off,
+                        s_part + ((((t / kTilesPerStep) & 1) * NWAVES + w) * kTilesPerStep + s) * kTileRows, g, l16);
                 }
             }
         }
         half ^= 1;
+    }
+    if (FUSED) {
+        __syncthreads();  // the last step's partial sums are complete
+        flush_column_sums(((ntiles - 1) / kTilesPerStep) * kTilesPerStep);
     }
 
     if (!wave_active) return;
@@ -495,17 +568,17 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
     flush(ntiles - 1);
 }
 
-template <int E, int NQB, int NWAVES>
+template <int E, int NQB, int NWAVES, bool FUSED = false>
 static int32_t launch_attn_variant(const AttnParams& p, int64_t units, hipStream_t s) {
     constexpr int lds = kStages * 2 * kTileRows * E * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES>,
+        if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return CHIPMUNK_ERR_LAUNCH;
         attr_set = true;
     }
-    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB, NWAVES>), dim3((unsigned)units), dim3(64 * NWAVES), lds, s, p);
+    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>), dim3((unsigned)units), dim3(64 * NWAVES), lds, s, p);
     return launch_status();
 }
 
@@ -514,6 +587,13 @@ static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_
     if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4>(p, units, s);
     if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4>(p, units, s);
     return launch_attn_variant<64, 2, 4>(p, units, s);
+}
+
+static int32_t launch_attn_fused(const AttnParams& p, int E, int64_t units, hipStream_t s) {
+    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4, true>(p, units, s);
+    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4, true>(p, units, s);
+    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4, true>(p, units, s);
+    return launch_attn_variant<64, 2, 4, true>(p, units, s);
 }
 
 static int32_t launch_colsum(const ColsumParams& cp, int E, int64_t units, hipStream_t s) {
@@ -550,6 +630,7 @@ extern "C" int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t*
     AttnParams p;
     p.q = q; p.k = k; p.v = v; p.base = base; p.out = out; p.idx = idx; p.counts = counts;
     p.row_m = nullptr; p.row_l = nullptr;
+    p.prev_m = nullptr; p.prev_l = nullptr; p.colsum = nullptr; p.ld_colsum = 0;
     p.N = N; p.NB = NB; p.c = c; p.k_stride = k_stride;
     p.sl2 = softmax_scale * 1.4426950408889634f;
     p.o_scale = o_scale;
@@ -582,6 +663,7 @@ extern "C" int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, con
     p.q = q; p.k = k; p.v = v; p.base = nullptr; p.out = out; p.idx = nullptr; p.counts = nullptr;
     p.row_m = colsum ? (float*)ws : nullptr;
     p.row_l = colsum ? (float*)ws + (int64_t)B * H * N : nullptr;
+    p.prev_m = nullptr; p.prev_l = nullptr; p.colsum = nullptr; p.ld_colsum = 0;
     p.N = N; p.NB = NB; p.c = c; p.k_stride = 0;
     p.sl2 = softmax_scale * 1.4426950408889634f;
     p.o_scale = 1.f;
@@ -611,4 +693,32 @@ extern "C" int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t*
     cp.q = q; cp.k = k; cp.row_m = prev_m; cp.row_l = prev_l; cp.colsum = colsum; cp.ld = ld_colsum;
     cp.N = N; cp.NB = NB; cp.c = c; cp.sl2 = softmax_scale * 1.4426950408889634f;
     return launch_colsum(cp, E, units, (hipStream_t)stream);
+}
+
+extern "C" int32_t chipmunk_attn_dense_colsum_stale(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                                                    uint16_t* out, const float* prev_m, const float* prev_l,
+                                                    float* colsum, int64_t ld_colsum, float* new_m, float* new_l,
+                                                    int B, int H, int N, int E, int c, float softmax_scale,
+                                                    void* stream) {
+    if (!q || !k || !v || !out || !prev_m || !prev_l || !colsum) return CHIPMUNK_ERR_NULL;
+    if ((new_m == nullptr) != (new_l == nullptr)) return CHIPMUNK_ERR_NULL;
+    if (B < 1 || H < 1 || N < 1 || ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
+    if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return CHIPMUNK_ERR_SHAPE;
+    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(colsum) || (ld_colsum % 4) != 0)
+        return CHIPMUNK_ERR_ALIGN;
+    for (const float* f : {prev_m, prev_l, (const float*)new_m, (const float*)new_l})
+        if (reinterpret_cast<uintptr_t>(f) & 3u) return CHIPMUNK_ERR_ALIGN;
+    int NB = (N + c - 1) / c;
+    int64_t units = (int64_t)B * H * NB;
+    if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
+    AttnParams p;
+    p.q = q; p.k = k; p.v = v; p.base = nullptr; p.out = out; p.idx = nullptr; p.counts = nullptr;
+    p.row_m = new_m; p.row_l = new_l;
+    p.prev_m = prev_m; p.prev_l = prev_l; p.colsum = colsum; p.ld_colsum = ld_colsum;
+    p.N = N; p.NB = NB; p.c = c; p.k_stride = 0;
+    p.sl2 = softmax_scale * 1.4426950408889634f;
+    p.o_scale = 1.f;
+    return launch_attn_fused(p, E, units, (hipStream_t)stream);
 }

@@ -3,7 +3,9 @@
 Step 1 is dense and fills every cache (Alg. 2 and Alg. 5 of the paper): dense attention with exact column sums,
 top-k of the column sums, O_cache = O_dense - delta (the sparse-delta call with o_scale = -1), dense MLP with A_cache
 and M_cache, token-merged pre-activations T_m.  Later steps are column-sparse (Alg. 3, 6, 7): attention delta with the
-cached indices, then T = mean_c(x) W1^T, top-k of |T - T_m|, MLP delta.
+cached indices, then T = mean_c(x) W1^T, top-k of |T - T_m|, MLP delta.  A later dense step (a cache refresh) takes
+its column sums in the same kernel as the attention, against the softmax normalisers the previous dense step left
+(Alg. 4), and leaves its own for the next refresh.
 
 With `overlap`, the index computation of the NEXT block (scores GEMM + top-k, which depend only on that block's input
 and weights) runs on a second stream beside the current block's attention and MLP delta; an event hands the indices
@@ -14,7 +16,8 @@ import math
 
 import torch
 
-from . import (ACT_GELU_TANH, attn_dense, attn_dense_workspace_bytes, attn_sparse_delta, mlp_dense,
+from . import (ACT_GELU_TANH, attn_dense, attn_dense_colsum_stale, attn_dense_row_stats,
+               attn_dense_workspace_bytes, attn_sparse_delta, mlp_dense,
                mlp_sparse_delta, mlp_tile_mean_preact, mlp_tile_mean_workspace_bytes, mlp_workspace_bytes,
                topk_cols)
 
@@ -47,12 +50,23 @@ class Block:
         self.T = torch.empty_like(self.T_m)
         self.ws_tm = _u8(mlp_tile_mean_workspace_bytes(B, N, D, F, c), dev)
         self.ws_mlp = _u8(mlp_workspace_bytes(B, N, D, F, c, max(k_mlp, 1)), dev)
+        self.row_m = torch.empty((B, H, N), dtype=torch.float32, device=dev)   # softmax normalisers of the last
+        self.row_l = torch.empty_like(self.row_m)                              # dense step (valid once has_stats)
+        self.has_stats = False
 
     def dense_step(self, step, colsum, ws_attn):
         """Alg. 2 + Alg. 5 on the inputs of `step`; colsum [B,H,NB,ld] fp32 and ws_attn are shared scratch."""
         i = self.inputs
         q, k, v, x = i["q"][step], i["k"][step], i["v"][step], i["x"][step]
-        attn_dense(q, k, v, self.attn_out, colsum, self.c, self.scale, ws_attn)
+        if self.has_stats:   # Alg. 4: one kernel; the normalisers are replaced row by row by the workgroup that read them
+            attn_dense_colsum_stale(q, k, v, self.attn_out, self.row_m, self.row_l, colsum, self.c, self.scale,
+                                    self.row_m, self.row_l)
+        else:
+            attn_dense(q, k, v, self.attn_out, colsum, self.c, self.scale, ws_attn)
+            m, l = attn_dense_row_stats(ws_attn, self.B, self.H, self.N)
+            self.row_m.copy_(m)
+            self.row_l.copy_(l)
+            self.has_stats = True
         topk_cols(colsum.view(-1, colsum.shape[-1])[:, :self.N], None, self.k_attn,
                   self.idx_a.view(-1, self.idx_a.shape[-1]), self.cnt_a.view(-1))
         attn_sparse_delta(q, k, v, self.idx_a, self.cnt_a, self.attn_out, self.o_cache, self.c, self.scale, -1.0)

@@ -273,6 +273,44 @@ def test_attn_colsum_with_stale_normalisers_parity(cm, oracle, B, H, N, E, c):
     assert overlap >= 0.9      # the approximation App. B.2 relies on: stale normalisers barely move the top-k set
 
 
+@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (2, 2, 700, 128, 192), (1, 1, 100, 128, 128)])
+def test_attn_dense_fused_with_stale_column_sums_parity(cm, oracle, B, H, N, E, c):
+    """Alg. 4 in one kernel: dense output, column sums against the previous step's normalisers, and this step's
+    normalisers for the next one."""
+    (q1, k1, v1), (q2, k2, v2), _ = si.attn_steps(B, H, N, E, 11, DEV)
+    scale = 1.0 / math.sqrt(E)
+    NB = -(-N // c)
+    ld = -(-N // 4) * 4
+    out1 = torch.empty_like(q1)
+    D1 = torch.empty((B, H, NB, ld), dtype=torch.float32, device=DEV)
+    ws = _u8(cm.attn_dense_workspace_bytes(B, H, N))
+    cm.attn_dense(q1, k1, v1, out1, D1, c, scale, ws)                    # step 1: leaves (m, l)
+    m1, l1 = (t.clone() for t in cm.attn_dense_row_stats(ws, B, H, N))
+    out2 = torch.empty_like(q2)
+    D2 = torch.full((B, H, NB, ld), -1.0, dtype=torch.float32, device=DEV)
+    m2 = torch.empty_like(m1)
+    l2 = torch.empty_like(l1)
+    cm.attn_dense_colsum_stale(q2, k2, v2, out2, m1, l1, D2, c, scale, m2, l2)   # step 2
+    qn, kn, vn = si.np_f32(q2), si.np_f32(k2), si.np_f32(v2)
+    assert rel_err(si.np_f32(out2), oracle.attn_dense(qn, kn, vn, c, scale)) <= REL_TOL
+    ref = oracle.attn_colsum_stale(qn, kn, m1.cpu().numpy().astype(np.float64), l1.cpu().numpy().astype(np.float64), c, scale)
+    got = D2.cpu().numpy()
+    assert rel_err(got[..., :N].astype(np.float64), ref) <= REL_TOL
+    assert (got[..., N:] == -1.0).all()
+    m_ref, l_ref = oracle.attn_row_stats(qn, kn, scale)
+    lse = m2.cpu().numpy().astype(np.float64) + np.log(l2.cpu().numpy().astype(np.float64))
+    assert np.abs(lse - (m_ref + np.log(l_ref))).max() <= 2e-3
+    # the separate pass over the same inputs gives the same sums
+    D2b = torch.empty_like(D2)
+    cm.attn_colsum_stale(q2, k2, m1, l1, D2b, c, scale)
+    assert rel_err(got[..., :N].astype(np.float64), D2b.cpu().numpy()[..., :N].astype(np.float64)) <= 1e-3
+    # without the statistics outputs
+    out3 = torch.empty_like(q2)
+    D3 = torch.empty_like(D2)
+    cm.attn_dense_colsum_stale(q2, k2, v2, out3, m1, l1, D3, c, scale)
+    assert torch.equal(out3, out2) and torch.equal(D3[..., :N], D2[..., :N])
+
+
 def _check_sampled_attn_units(cm, oracle, name, n_units, sparse_k):
     cfg = si.CONFIGS[name]
     B, H, E, c = cfg["B"], cfg["H"], cfg["E"], cfg["c"]
@@ -316,7 +354,8 @@ def test_attn_wan_shape_sampled_units(cm, oracle):
 
 def test_attn_dense_and_column_sums_hunyuan_shape_sampled_units(cm, oracle):
     """The dense step at the full HunyuanVideo shape (the launch bench.py uses to fill the caches): output, exact
-    column sums and the stale-normaliser column sums of sampled chunks against the oracle."""
+    column sums and the stale-normaliser column sums (as a pass of their own and from the attention kernel) of
+    sampled chunks against the oracle."""
     cfg = si.CONFIGS["hunyuan"]
     B, H, E, c = cfg["B"], cfg["H"], cfg["E"], cfg["c"]
     N = si.config_tokens(cfg)
@@ -333,6 +372,10 @@ def test_attn_dense_and_column_sums_hunyuan_shape_sampled_units(cm, oracle):
     m, l = cm.attn_dense_row_stats(ws, B, H, N)
     D2 = torch.empty_like(D)
     cm.attn_colsum_stale(q2, k2, m, l, D2, c, scale)
+    out3 = torch.empty_like(q2)
+    D3 = torch.empty_like(D)
+    m3, l3 = torch.empty_like(m), torch.empty_like(l)
+    cm.attn_dense_colsum_stale(q2, k2, v, out3, m, l, D3, c, scale, m3, l3)
     torch.cuda.synchronize()
     for b, h, i in [(0, 0, 0), (B - 1, H - 1, NB - 1), (0, H // 2, NB // 3)]:
         rows = slice(i * c, min(N, (i + 1) * c))
@@ -345,6 +388,12 @@ def test_attn_dense_and_column_sums_hunyuan_shape_sampled_units(cm, oracle):
         ref2 = oracle.attn_colsum_stale(si.np_f32(q2[b:b + 1, h:h + 1, rows]), si.np_f32(k2[b:b + 1, h:h + 1]), ms, ls, c,
                                         scale)
         assert rel_err(D2[b, h, i, :N].cpu().numpy().astype(np.float64), ref2[0, 0, 0]) <= REL_TOL, (b, h, i)
+        assert rel_err(D3[b, h, i, :N].cpu().numpy().astype(np.float64), ref2[0, 0, 0]) <= REL_TOL, (b, h, i)
+        q2n, k2n = si.np_f32(q2[b:b + 1, h:h + 1, rows]), si.np_f32(k2[b:b + 1, h:h + 1])
+        assert rel_err(si.np_f32(out3[b:b + 1, h:h + 1, rows]), oracle.attn_dense(q2n, k2n, vn, c, scale)) <= REL_TOL
+        m_ref, l_ref = oracle.attn_row_stats(q2n, k2n, scale)
+        lse = (m3[b, h, rows].cpu().numpy().astype(np.float64) + np.log(l3[b, h, rows].cpu().numpy().astype(np.float64)))
+        assert np.abs(lse - (m_ref + np.log(l_ref))[0, 0]).max() <= 2e-3, (b, h, i)
 
 
 # ---------------------------------------------------------------------- MLP ---

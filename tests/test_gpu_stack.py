@@ -137,3 +137,53 @@ def test_stack_sparse_step_as_hip_graph():
         restore()
         stack.sparse_step(blocks, 1)    # eager work between the replays
         assert same(snapshot(), eager), f"eager run after replay {replay}"
+
+
+def test_stack_dense_refresh_with_stale_normalisers(oracle):
+    """Dense step, sparse step, a second dense step (the cache refresh, Alg. 4: column sums against the first
+    dense step's normalisers, in the attention kernel), sparse step with the refreshed indices."""
+    import paper_2506_03275_amd as cm
+    from paper_2506_03275_amd import stack
+    cm.load()
+    cfg = si.CONFIGS["tiny"]
+    c, E = cfg["c"], cfg["E"]
+    N = si.config_tokens(cfg)
+    k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
+    inputs = si.stack_inputs(cfg, 2, 4, 13, DEV)
+    blocks = [stack.Block(inp, c, k_a, k_m) for inp in inputs]
+    scale = 1.0 / math.sqrt(E)
+    f32 = si.np_f32
+    stack.dense_step(blocks, 0)
+    stack.sparse_step(blocks, 1)
+    torch.cuda.synchronize()
+    ld = -(-N // 4) * 4
+    ws = torch.empty(max(cm.attn_dense_workspace_bytes(cfg["B"], cfg["H"], N), 16), dtype=torch.uint8, device=DEV)
+    for b, (blk, inp) in enumerate(zip(blocks, inputs)):
+        assert blk.has_stats
+        m0, l0 = blk.row_m.cpu().numpy().astype(np.float64), blk.row_l.cpu().numpy().astype(np.float64)
+        idx_before = blk.idx_a.clone()
+        colsum = torch.empty((cfg["B"], cfg["H"], blk.NB, ld), dtype=torch.float32, device=DEV)
+        blk.dense_step(2, colsum, ws)
+        torch.cuda.synchronize()
+        q, k, v = (f32(inp[n][2]) for n in "qkv")
+        dense_gpu = f32(blk.attn_out).astype(np.float64)
+        assert rel_err(dense_gpu, oracle.attn_dense(q, k, v, c, scale)) <= REL_TOL, b
+        got = colsum.cpu().numpy()[..., :N]
+        assert rel_err(got.astype(np.float64), oracle.attn_colsum_stale(q, k, m0, l0, c, scale)) <= REL_TOL, b
+        # the refreshed index lists are the exact top-k of the GPU's own column sums
+        ref_idx, ref_cnt = oracle.topk_cols(got.reshape(-1, N), None, k_a)
+        idx_a, cnt_a = blk.idx_a.cpu().numpy(), blk.cnt_a.cpu().numpy()
+        assert np.array_equal(idx_a.reshape(-1, k_a), ref_idx) and np.array_equal(cnt_a.reshape(-1), ref_cnt)
+        assert not torch.equal(idx_before, blk.idx_a)       # the inputs moved: so did the choice
+        # the statistics left for the next refresh are this step's own
+        m_ref, l_ref = oracle.attn_row_stats(q, k, scale)
+        lse = blk.row_m.cpu().numpy().astype(np.float64) + np.log(blk.row_l.cpu().numpy().astype(np.float64))
+        assert np.abs(lse - (m_ref + np.log(l_ref))).max() <= 2e-3
+        cache_gpu = f32(blk.o_cache).astype(np.float64)
+        o_cache = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, dense_gpu, c, scale, -1.0)
+        assert rel_err(cache_gpu - dense_gpu, o_cache - dense_gpu) <= REL_TOL, b
+        blk.attn_delta(3)
+        torch.cuda.synchronize()
+        q, k, v = (f32(inp[n][3]) for n in "qkv")
+        ref = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, cache_gpu, c, scale, 1.0)
+        assert rel_err(f32(blk.attn_out) - cache_gpu, ref - cache_gpu) <= REL_TOL, b

@@ -80,6 +80,11 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert cs(a, a, a, a, a, 100, 1, 1, 128, 128, 192, 0.1, None) == -2                # ld_colsum < N
     assert cs(a, a, a, a, a, 128, 1, 1, 128, 96, 192, 0.1, None) == -4                 # E
     assert cs(a, a, P(0x1002), a, a, 128, 1, 1, 128, 128, 192, 0.1, None) == -3        # fp32 alignment
+    fu = lib.chipmunk_attn_dense_colsum_stale
+    assert fu(a, a, a, a, None, a, a, 128, None, None, 1, 1, 128, 128, 192, 0.1, None) == -1   # normalisers required
+    assert fu(a, a, a, a, a, a, a, 128, a, None, 1, 1, 128, 128, 192, 0.1, None) == -1         # new_m without new_l
+    assert fu(a, a, a, a, a, a, a, 100, None, None, 1, 1, 128, 128, 192, 0.1, None) == -2      # ld_colsum < N
+    assert fu(a, a, a, a, a, a, a, 128, None, None, 1, 1, 128, 128, 160, 0.1, None) == -4      # c
 
 
 def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
