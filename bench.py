@@ -345,10 +345,10 @@ def ceilings_bench(dev):
     out["mfma_slots_tflops"] = {}
     for shape in (16, 32):
         for waves in (1, 2):
-            for group in (0, 1):
+            for head_dim in (0, 64, 128):                # softmax vector work per flop of that head dimension
                 it = 30000 // waves
-                ms = timed(lambda: cl.mfma_slots(shape, waves, group, it, sink))
-                name = f"{shape}x{shape}x{512 // shape}_waves{waves}_" + ("softmax_pair_per_32768_flop" if group else "alone")
+                ms = timed(lambda: cl.mfma_slots(shape, waves, head_dim, it, sink))
+                name = f"{shape}x{shape}x{512 // shape}_waves{waves}_" + (f"softmax_of_head_dim_{head_dim}" if head_dim else "alone")
                 out["mfma_slots_tflops"][name] = round(cl.mfma_slots_flops(waves, it) / (ms * 1e-3) / 1e12, 1)
     src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
     dst = torch.empty_like(src)

@@ -48,8 +48,8 @@ def mfma_slots_flops(blocks_per_cu, iters):
     return float(load().chipmunk_probe_mfma_slots_flops(blocks_per_cu, iters))
 
 
-def mfma_slots(shape, blocks_per_cu, with_vector_group, iters, sink):
-    _check(load().chipmunk_probe_mfma_slots(shape, blocks_per_cu, int(with_vector_group), iters, sink.data_ptr(),
+def mfma_slots(shape, blocks_per_cu, head_dim, iters, sink):
+    _check(load().chipmunk_probe_mfma_slots(shape, blocks_per_cu, int(head_dim), iters, sink.data_ptr(),
                                             _stream()), "chipmunk_probe_mfma_slots")
 
 

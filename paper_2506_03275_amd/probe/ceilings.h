@@ -25,11 +25,13 @@ double chipmunk_probe_mfma_flops(int blocks_per_cu, int iters);
 int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int valu_ops, int iters, float* sink, void* stream);
 
 /* The softmax-between-GEMMs instruction stream at its finest grain: every wave runs `iters` rounds of 24 slots, a
- * slot being 32768 flop of MFMA (one 32x32x16 or two 16x16x32, shape = 32 or 16) followed, when with_vector_group
- * is non-zero, by the vector work of one pair of probabilities (2 multiply-subtracts, 2 exponentials, 1 bf16 pack),
- * all pinned in that order.  chipmunk_probe_mfma_slots_flops gives the flop of one launch. */
+ * slot being 32768 flop of MFMA (one 32x32x16 or two 16x16x32, shape = 32 or 16).  head_dim = 64: every slot is
+ * followed by the vector work of one pair of probabilities (2 multiply-subtracts, 2 exponentials, 1 bf16 pack), all
+ * pinned in that order; head_dim = 128: every second slot (a score costs 4 * head_dim flop, so these are the
+ * softmax's vector instructions per flop at that head dimension); head_dim = 0: MFMAs alone.
+ * chipmunk_probe_mfma_slots_flops gives the flop of one launch. */
 double chipmunk_probe_mfma_slots_flops(int blocks_per_cu, int iters);
-int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int with_vector_group, int iters, float* sink,
+int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int head_dim, int iters, float* sink,
                                   void* stream);
 
 /* Reads `bytes` (multiple of 16) once with 16-byte loads, eight in flight per lane. */

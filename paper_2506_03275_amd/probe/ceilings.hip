@@ -66,11 +66,11 @@ __global__ __launch_bounds__(256) void mfma32_kernel(float* sink, int iters) {
     sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// One MFMA followed by the vector work of one pair of softmax probabilities (two multiply-subtracts, two
-// exponentials, one bf16 pack), every instruction pinned in place by inline assembly.  SHAPE 32: the group follows
-// every 32x32x16 MFMA; SHAPE 16: every second 16x16x32 MFMA (the same vector work per flop).  GROUP = false leaves
-// the MFMAs alone.
-template <int SHAPE, bool GROUP>
+// Slots of 32768 flop of MFMA (one 32x32x16 or two 16x16x32), every EVERY-th slot followed by the vector work of
+// one pair of softmax probabilities (two multiply-subtracts, two exponentials, one bf16 pack), every instruction
+// pinned in place by inline assembly.  A score costs 4 E flop (E = head dimension), so one pair per slot is the
+// softmax work per flop of E = 64 and one pair per two slots that of E = 128.  EVERY = 0 leaves the MFMAs alone.
+template <int SHAPE, int EVERY>
 __global__ __launch_bounds__(256) void mfma_slot_kernel(float* sink, int iters) {
     bf16x8 a, b;
     probe_operands(a, b);
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void mfma_slot_kernel(float* sink, int iters) 
                 asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc16[(2 * s) % 12]) : "v"(a), "v"(b));
                 asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc16[(2 * s + 1) % 12]) : "v"(a), "v"(b));
             }
-            if (GROUP) {
+            if (EVERY > 0 && s % (EVERY > 0 ? EVERY : 1) == 0) {
                 float x0, x1;
                 uint32_t pk;
                 asm volatile("v_fma_f32 %0, %2, %4, -%5\n\tv_fma_f32 %1, %3, %4, -%5"
@@ -187,19 +187,23 @@ extern "C" double chipmunk_probe_mfma_slots_flops(int blocks_per_cu, int iters) 
     return 24.0 * 32 * 32 * 16 * 2 * 4.0 * (double)compute_units() * blocks_per_cu * iters;
 }
 
-extern "C" int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int with_vector_group, int iters, float* sink,
+extern "C" int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int head_dim, int iters, float* sink,
                                              void* stream) {
     if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2) || (shape != 16 && shape != 32)) return -1;
+    if (head_dim != 0 && head_dim != 64 && head_dim != 128) return -1;
     const int cus = compute_units();
     if (cus < 1) return -6;
     dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
     hipStream_t s = (hipStream_t)stream;
+    const int every = head_dim == 0 ? 0 : head_dim / 64;
     if (shape == 32) {
-        if (with_vector_group) hipLaunchKernelGGL((mfma_slot_kernel<32, true>), grid, block, 0, s, sink, iters);
-        else hipLaunchKernelGGL((mfma_slot_kernel<32, false>), grid, block, 0, s, sink, iters);
+        if (every == 0) hipLaunchKernelGGL((mfma_slot_kernel<32, 0>), grid, block, 0, s, sink, iters);
+        else if (every == 1) hipLaunchKernelGGL((mfma_slot_kernel<32, 1>), grid, block, 0, s, sink, iters);
+        else hipLaunchKernelGGL((mfma_slot_kernel<32, 2>), grid, block, 0, s, sink, iters);
     } else {
-        if (with_vector_group) hipLaunchKernelGGL((mfma_slot_kernel<16, true>), grid, block, 0, s, sink, iters);
-        else hipLaunchKernelGGL((mfma_slot_kernel<16, false>), grid, block, 0, s, sink, iters);
+        if (every == 0) hipLaunchKernelGGL((mfma_slot_kernel<16, 0>), grid, block, 0, s, sink, iters);
+        else if (every == 1) hipLaunchKernelGGL((mfma_slot_kernel<16, 1>), grid, block, 0, s, sink, iters);
+        else hipLaunchKernelGGL((mfma_slot_kernel<16, 2>), grid, block, 0, s, sink, iters);
     }
     return status();
 }

@@ -102,7 +102,8 @@ def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
     assert lib.chipmunk_probe_mfma_bf16(16, 1, 0, 10, None, None) == -1
     assert lib.chipmunk_probe_mfma_bf16(24, 1, 0, 10, a, None) == -1      # shape
     assert lib.chipmunk_probe_mfma_bf16(32, 1, 32, 10, a, None) == -1     # valu_ops
-    assert lib.chipmunk_probe_mfma_slots(8, 1, 1, 10, a, None) == -1      # shape
+    assert lib.chipmunk_probe_mfma_slots(8, 1, 64, 10, a, None) == -1     # shape
+    assert lib.chipmunk_probe_mfma_slots(16, 1, 1, 10, a, None) == -1     # head dimension of the vector mix
     assert lib.chipmunk_probe_mfma_slots_flops(1, 0) == 0.0
     assert lib.chipmunk_probe_read(a, 24, a, None) == -1                  # bytes % 16
     assert lib.chipmunk_probe_copy(a, P(0x2008), 64, None) == -1          # alignment
