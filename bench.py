@@ -350,6 +350,11 @@ def ceilings_bench(dev):
                 ms = timed(lambda: cl.mfma_bf16(shape, waves, valu, iters // waves, sink))
                 name = f"{shape}x{shape}x{512 // shape}_waves{waves}_valu{valu}"
                 out["mfma_bf16_tflops"][name] = round(cl.mfma_flops(waves, iters // waves) / (ms * 1e-3) / 1e12, 1)
+    out["mfma_phase_length_tflops"] = {}               # 16x16x32, two waves per SIMD, 60 FMAs per 24 MFMAs
+    for per_phase in (24, 12, 8, 4, 2):
+        ms = timed(lambda: cl.mfma_phases(per_phase, 2, iters // 2, sink))
+        out["mfma_phase_length_tflops"][f"{per_phase}_mfmas_per_phase"] = round(
+            cl.mfma_flops(2, iters // 2) / (ms * 1e-3) / 1e12, 1)
     out["mfma_slots_tflops"] = {}
     for shape in (16, 32):
         for waves in (1, 2):

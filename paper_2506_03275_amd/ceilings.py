@@ -18,6 +18,7 @@ def load():
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         lib.chipmunk_probe_mfma_flops.argtypes, lib.chipmunk_probe_mfma_flops.restype = [i32, i32], ctypes.c_double
         lib.chipmunk_probe_mfma_bf16.argtypes, lib.chipmunk_probe_mfma_bf16.restype = [i32] * 4 + [vp, vp], ctypes.c_int32
+        lib.chipmunk_probe_mfma_phases.argtypes, lib.chipmunk_probe_mfma_phases.restype = [i32] * 3 + [vp, vp], ctypes.c_int32
         lib.chipmunk_probe_mfma_slots_flops.argtypes, lib.chipmunk_probe_mfma_slots_flops.restype = [i32, i32], ctypes.c_double
         lib.chipmunk_probe_mfma_slots.argtypes, lib.chipmunk_probe_mfma_slots.restype = [i32] * 4 + [vp, vp], ctypes.c_int32
         lib.chipmunk_probe_read.argtypes, lib.chipmunk_probe_read.restype = [vp, sz, vp, vp], ctypes.c_int32
@@ -42,6 +43,11 @@ def mfma_flops(blocks_per_cu, iters):
 def mfma_bf16(shape, blocks_per_cu, valu_ops, iters, sink):
     _check(load().chipmunk_probe_mfma_bf16(shape, blocks_per_cu, valu_ops, iters, sink.data_ptr(), _stream()),
            "chipmunk_probe_mfma_bf16")
+
+
+def mfma_phases(mfmas_per_phase, blocks_per_cu, iters, sink):
+    _check(load().chipmunk_probe_mfma_phases(mfmas_per_phase, blocks_per_cu, iters, sink.data_ptr(), _stream()),
+           "chipmunk_probe_mfma_phases")
 
 
 def mfma_slots_flops(blocks_per_cu, iters):

@@ -24,6 +24,12 @@ double chipmunk_probe_mfma_flops(int blocks_per_cu, int iters);
  *   sink: at least 2 * 256 * (number of compute units) floats, written once per thread */
 int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int valu_ops, int iters, float* sink, void* stream);
 
+/* The stream of chipmunk_probe_mfma_bf16(16, blocks_per_cu, ~64, ...) with its two phases cut finer: every round is
+ * 24 / mfmas_per_phase times [mfmas_per_phase x v_mfma_f32_16x16x32_bf16 | 60 * mfmas_per_phase / 24 fp32 FMAs]
+ * (the same work per round whatever the cut).  mfmas_per_phase: 24, 12, 8, 4 or 2.  Flop of one launch:
+ * chipmunk_probe_mfma_flops(blocks_per_cu, iters). */
+int32_t chipmunk_probe_mfma_phases(int mfmas_per_phase, int blocks_per_cu, int iters, float* sink, void* stream);
+
 /* The softmax-between-GEMMs instruction stream at its finest grain: every wave runs `iters` rounds of 24 slots, a
  * slot being 32768 flop of MFMA (one 32x32x16 or two 16x16x32, shape = 32 or 16).  head_dim = 64: every slot is
  * followed by the vector work of one pair of probabilities (2 multiply-subtracts, 2 exponentials, 1 bf16 pack), all

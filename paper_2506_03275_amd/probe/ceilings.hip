@@ -66,6 +66,31 @@ __global__ __launch_bounds__(256) void mfma32_kernel(float* sink, int iters) {
     sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The stream of mfma16_kernel<60> cut into finer phases: NM 16x16x32 MFMAs, then 60 * NM / 24 FMAs, 24 / NM times
+// per round.
+template <int NM>
+__global__ __launch_bounds__(256) void mfma16_phases_kernel(float* sink, int iters) {
+    bf16x8 a, b;
+    probe_operands(a, b);
+    f32x4 acc[24];
+    for (int i = 0; i < 24; i++) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float v[8];
+    for (int i = 0; i < 8; i++) v[i] = threadIdx.x * 0.001f + i;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int ph = 0; ph < 24 / NM; ph++) {
+#pragma unroll
+            for (int i = 0; i < NM; i++)
+                acc[ph * NM + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[ph * NM + i], 0, 0, 0);
+            probe_valu<60 * NM / 24>(v);
+        }
+    }
+    float s = 0.f;
+    for (int i = 0; i < 24; i++) s += acc[i][0] + acc[i][3];
+    for (int i = 0; i < 8; i++) s += v[i];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 // Slots of 32768 flop of MFMA (one 32x32x16 or two 16x16x32), every EVERY-th slot followed by the vector work of
 // one pair of softmax probabilities (two multiply-subtracts, two exponentials, one bf16 pack), every instruction
 // pinned in place by inline assembly.  A score costs 4 E flop (E = head dimension), so one pair per slot is the
@@ -178,6 +203,23 @@ extern "C" int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int va
         if (valu_ops == 0) hipLaunchKernelGGL(mfma32_kernel<0>, grid, block, 0, s, sink, iters);
         else if (valu_ops == 64) hipLaunchKernelGGL(mfma32_kernel<64>, grid, block, 0, s, sink, iters);
         else hipLaunchKernelGGL(mfma32_kernel<128>, grid, block, 0, s, sink, iters);
+    }
+    return status();
+}
+
+extern "C" int32_t chipmunk_probe_mfma_phases(int mfmas_per_phase, int blocks_per_cu, int iters, float* sink, void* stream) {
+    if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2)) return -1;
+    const int cus = compute_units();
+    if (cus < 1) return -6;
+    dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
+    hipStream_t s = (hipStream_t)stream;
+    switch (mfmas_per_phase) {
+        case 24: hipLaunchKernelGGL(mfma16_phases_kernel<24>, grid, block, 0, s, sink, iters); break;
+        case 12: hipLaunchKernelGGL(mfma16_phases_kernel<12>, grid, block, 0, s, sink, iters); break;
+        case 8: hipLaunchKernelGGL(mfma16_phases_kernel<8>, grid, block, 0, s, sink, iters); break;
+        case 4: hipLaunchKernelGGL(mfma16_phases_kernel<4>, grid, block, 0, s, sink, iters); break;
+        case 2: hipLaunchKernelGGL(mfma16_phases_kernel<2>, grid, block, 0, s, sink, iters); break;
+        default: return -1;
     }
     return status();
 }
