@@ -209,6 +209,9 @@ extern "C" int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int va
 
 extern "C" int32_t chipmunk_probe_mfma_phases(int mfmas_per_phase, int blocks_per_cu, int iters, float* sink, void* stream) {
     if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2)) return -1;
+    if (mfmas_per_phase != 24 && mfmas_per_phase != 12 && mfmas_per_phase != 8 && mfmas_per_phase != 4 &&
+        mfmas_per_phase != 2)
+        return -1;
     const int cus = compute_units();
     if (cus < 1) return -6;
     dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
