@@ -249,7 +249,7 @@ def cpu_baseline(st, budget_s=20.0):
 
 
 def stack_bench(cm, args, steps, warmup, dev):
-    """BASELINE config 4: 4 HunyuanVideo-shaped blocks x 3 diffusion steps.  A timed "step" here is one pass of the
+    """The layer-stack workload: 4 HunyuanVideo-shaped blocks x 3 diffusion steps.  A timed "step" here is one pass of the
     two column-sparse diffusion steps over the four blocks (8 block passes), with the next block's MLP index work
     on a side stream; the serial schedule and the dense step are timed beside it."""
     from paper_2506_03275_amd import stack

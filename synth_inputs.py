@@ -24,7 +24,7 @@ HOT_FRACTION = 0.15
 HOT_SIGMA = 0.1
 COLD_SIGMA = 0.01
 
-# name -> shapes of the benchmark's configs (0 Tiny, 1 FLUX, 2 HunyuanVideo, 3 WAN2.1-14B)
+# name -> shapes of the benchmark configurations (0 Tiny, 1 FLUX, 2 HunyuanVideo, 3 WAN2.1-14B)
 CONFIGS = {
     "tiny": dict(B=1, H=2, E=64, c=128, n_prefix=0, grid=(8, 8, 16), n_suffix=0, voxel=(4, 4, 8),
                  D=256, F=1024, attn_keep=0.25, mlp_keep=0.25),
@@ -158,7 +158,7 @@ def np_bf16_round(a):
 
 
 def stack_inputs(cfg, n_blocks, n_steps, seed, device="cpu"):
-    """Inputs of a stack of DiT blocks over consecutive diffusion steps (BASELINE config 4).
+    """Inputs of a stack of DiT blocks over consecutive diffusion steps.
 
     Returns blocks[b] = dict(q, k, v, x: lists over steps of bf16 tensors; w1, b1, w2, b2).  Every block has its
     own draws; step t+1 is step t perturbed by the recipe above with the block's fixed set of hot key tokens.

@@ -1,4 +1,4 @@
-"""The layer stack of BASELINE config 4 at a small shape: two blocks over three diffusion steps (one dense, two
+"""The layer stack (several DiT blocks over consecutive diffusion steps) at a small shape: two blocks over three diffusion steps (one dense, two
 column-sparse), with and without the side-stream overlap of the MLP index work, against the oracle chained the
 same way.  The oracle takes its index lists from the GPU run (top-k parity has its own bit-exact tests on a shared
 score buffer; here a borderline column chosen differently from slightly different scores would change what is
