@@ -248,6 +248,50 @@ def cpu_baseline(st, budget_s=20.0):
     }
 
 
+def library_context(st):
+    """Dense attention and dense MLP of the same shape through torch's own kernels (whatever SDPA backend and GEMM
+    library this build of torch picks): a second dense denominator beside this library's dense kernels.  A call that
+    torch cannot run at this shape is reported as null with the reason."""
+    import torch.nn.functional as F
+    out = {"note": "torch " + torch.__version__ + "; not part of the library or of `value`"}
+    rows = st["B"] * st["N"]
+
+    def timed(fn, reps=2):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    try:
+        from torch.nn.attention import SDPBackend, sdpa_kernel
+        with sdpa_kernel([SDPBackend.FLASH_ATTENTION, SDPBackend.EFFICIENT_ATTENTION]):   # never the N x N fallback
+            ms = timed(lambda: F.scaled_dot_product_attention(st["q"], st["k"], st["v"], scale=st["scale"]))
+        out["sdpa_ms"] = ms
+        out["sdpa_tflops"] = 4.0 * st["E"] * st["H"] * rows * st["N"] / (ms * 1e-3) / 1e12
+    except Exception as e:  # noqa: BLE001 (context only: report and go on)
+        out["sdpa_ms"] = None
+        out["sdpa_error"] = f"{type(e).__name__}: {str(e)[:200]}"
+    try:
+        x, w1, b1, w2, b2 = st["x"], st["w1"], st["b1"], st["w2"], st["b2"]
+
+        def mlp():
+            h = F.gelu(F.linear(x, w1, b1), approximate="tanh")
+            return torch.matmul(h, w2) + b2
+
+        ms = timed(mlp)
+        out["mlp_ms"] = ms
+        out["mlp_tflops"] = 4.0 * st["D"] * rows * st["F"] / (ms * 1e-3) / 1e12
+    except Exception as e:  # noqa: BLE001
+        out["mlp_ms"] = None
+        out["mlp_error"] = f"{type(e).__name__}: {str(e)[:200]}"
+    return out
+
+
 def stack_bench(cm, args, steps, warmup, dev):
     """The layer-stack workload: 4 HunyuanVideo-shaped blocks x 3 diffusion steps.  A timed "step" here is one pass of the
     two column-sparse diffusion steps over the four blocks (8 block passes), with the next block's MLP index work
@@ -383,6 +427,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--library-context", action="store_true",
+                    help="also time torch's own dense attention (SDPA) and dense MLP (matmul) at the same shape: "
+                         "context for the dense denominator, never used by the library or by `value`")
     ap.add_argument("--index-structures", action="store_true",
                     help="also time the attention kernel alone on two other index structures of the same size: "
                          "columns drawn uniformly per chunk, and whole blocks of 128 consecutive columns")
@@ -512,6 +559,19 @@ def main():
             "whole_step": (d_attn + d_mlp) / ms_per_step,
         }
         del st["dense_out"], st["dense_a"]
+
+    if args.library_context:
+        ctx = library_context(st)
+        if "dense" in extra:   # the speedups again, against the faster dense implementation of each op
+            best_attn = min(x for x in (extra["dense"]["attn_ms"], ctx.get("sdpa_ms")) if x)
+            best_mlp = min(x for x in (extra["dense"]["mlp_ms"], ctx.get("mlp_ms")) if x)
+            ctx["speedup_vs_faster_dense"] = {
+                "attn_kernel": best_attn / attn_ms,
+                "mlp_kernels": best_mlp / stages["mlp_sparse_delta"],
+                "attn_plus_mlp_kernels": (best_attn + best_mlp) / (attn_ms + stages["mlp_sparse_delta"]),
+                "whole_step": (best_attn + best_mlp) / ms_per_step,
+            }
+        extra["library_context"] = ctx
 
     line = {
         "metric": "sparse-delta attn+MLP useful TFLOP/s (whole step: reorder, top-k, scores, attention and MLP deltas)",
