@@ -273,7 +273,8 @@ def test_attn_colsum_with_stale_normalisers_parity(cm, oracle, B, H, N, E, c):
     assert overlap >= 0.9      # the approximation App. B.2 relies on: stale normalisers barely move the top-k set
 
 
-@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (2, 2, 700, 128, 192), (1, 1, 100, 128, 128)])
+@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (2, 2, 700, 128, 192), (1, 1, 100, 128, 128),
+                                       (1, 2, 333, 64, 192), (1, 1, 1, 128, 192)])
 def test_attn_dense_fused_with_stale_column_sums_parity(cm, oracle, B, H, N, E, c):
     """Alg. 4 in one kernel: dense output, column sums against the previous step's normalisers, and this step's
     normalisers for the next one."""
