@@ -88,6 +88,12 @@ __device__ __forceinline__ float rows4_sum(float x) {
 
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
+// Workgroup barrier for data exchanged through LDS: waits for this wave's LDS accesses only, so that loads from
+// global memory into registers stay in flight across it (__syncthreads() waits for those as well).
+__device__ __forceinline__ void lds_accesses_then_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory");
+}
+
 // ---- host side ---------------------------------------------------------------
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -195,66 +195,76 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     }
 
     // ---- epilogue: bias, activation, bf16, transpose to [neuron][token] through LDS ----
-    __syncthreads();  // every wave is done with the stage buffers
+    constexpr int CPR = BM / 8;                  // 16-byte chunks (8 tokens) per neuron row
+    constexpr int ITEMS = kBN * CPR / 256;       // (neuron, 8 tokens) cells per thread
+    static_assert(kBN * CPR % 256 == 0, "the tile's cells must divide over the threads");
+    // The cached activations of this thread's cells are requested here, ahead of the activation arithmetic and
+    // the transposition, so that their latency is paid once and in the shadow of that work.  One 16-byte load per
+    // cell whatever the case (cells past the end of the row or of the list read a valid address and are not
+    // used): a_ld is a multiple of 8 and at least N, so a cell that starts below N ends inside its row.
+    // bias of the lane's two neuron columns: requested first (the activation arithmetic waits for these only) and
+    // without a branch (w1 stands in as a valid address when there is no bias)
+    const uint16_t* bias_src = p.b1 ? p.b1 : p.w1;
+    uint16_t bias_raw[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) bias_raw[nt] = bias_src[s_neuron[wn * 64 + nt * 32 + l32]];
+    u32x4 old8[ITEMS];
+    if (MODE == kSparseDelta) {
+#pragma unroll
+        for (int n = 0; n < ITEMS; n++) {
+            const int item = tid + n * 256;
+            const int nl = item / CPR, ch = item - nl * CPR;
+            const int tok0 = row0 + ch * 8;
+            const uint16_t* arow = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + (tok0 < p.N ? tok0 : 0);
+            old8[n] = *reinterpret_cast<const u32x4*>(arow);
+        }
+    }
+    lds_accesses_then_barrier();  // every wave is done with the stage buffers
+    float bias[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++) bias[nt] = p.b1 ? bf16_bits_to_float(bias_raw[nt]) : 0.f;
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
         int nl = wn * 64 + nt * 32 + l32;
-        float bias = p.b1 ? bf16_bits_to_float(p.b1[s_neuron[nl]]) : 0.f;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll
             for (int rg = 0; rg < 4; rg++) {
                 int tl = wm * (BM / 2) + mt * 32 + rg * 8 + h * 4;
-                float a0 = gelu(acc[mt][nt][rg * 4 + 0] + bias, p.act);
-                float a1 = gelu(acc[mt][nt][rg * 4 + 1] + bias, p.act);
-                float a2 = gelu(acc[mt][nt][rg * 4 + 2] + bias, p.act);
-                float a3 = gelu(acc[mt][nt][rg * 4 + 3] + bias, p.act);
+                float a0 = gelu(acc[mt][nt][rg * 4 + 0] + bias[nt], p.act);
+                float a1 = gelu(acc[mt][nt][rg * 4 + 1] + bias[nt], p.act);
+                float a2 = gelu(acc[mt][nt][rg * 4 + 2] + bias[nt], p.act);
+                float a3 = gelu(acc[mt][nt][rg * 4 + 3] + bias[nt], p.act);
                 u32x2 v = {pack_bf16x2(a0, a1), pack_bf16x2(a2, a3)};
                 *reinterpret_cast<u32x2*>(smem + nl * TS + tl * 2) = v;
             }
     }
-    __syncthreads();
-    constexpr int CPR = BM / 8;  // 16-byte chunks (8 tokens) per neuron row
-    for (int item = tid; item < kBN * CPR; item += 256) {
+    lds_accesses_then_barrier();
+#pragma unroll
+    for (int n = 0; n < ITEMS; n++) {
+        const int item = tid + n * 256;
         int nl = item / CPR, ch = item - nl * CPR;
         int s = col0 + nl;
         int tok0 = row0 + ch * 8;
         int nvalid = min(8, p.N - tok0);
-        if (nvalid <= 0) {
-            if (MODE == kSparseDelta && s < p.k_pad)
-                *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = u32x4{0, 0, 0, 0};
-            continue;
-        }
-        if (s >= count) {  // padding rows of the contraction must read as zero in GEMM2
+        if (nvalid <= 0 || s >= count) {  // no such tokens, or a padding row of the contraction: it must read as zero in GEMM2
             if (MODE == kSparseDelta && s < p.k_pad)
                 *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = u32x4{0, 0, 0, 0};
             continue;
         }
         u32x4 a8 = *reinterpret_cast<const u32x4*>(smem + nl * TS + ch * 16);
         uint16_t* arow = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + tok0;
-        if (MODE == kDenseAct) {
-            if (nvalid == 8) {
-                *reinterpret_cast<u32x4*>(arow) = a8;
-            } else {
-                for (int e = 0; e < nvalid; e++) arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
-            }
-            continue;
-        }
-        u32x4 old8 = u32x4{0, 0, 0, 0};
         if (nvalid == 8) {
-            old8 = *reinterpret_cast<const u32x4*>(arow);
             *reinterpret_cast<u32x4*>(arow) = a8;
-        } else {
-            for (int e = 0; e < nvalid; e++) {
-                old8[e >> 1] |= (uint32_t)arow[e] << (16 * (e & 1));
-                arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
-            }
+        } else {  // the cells past N in the last chunk stay as they are
+            for (int e = 0; e < nvalid; e++) arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
         }
+        if (MODE == kDenseAct) continue;
         u32x4 d8;
 #pragma unroll
         for (int e2 = 0; e2 < 4; e2++) {
-            float dlo = bf16_bits_to_float(a8[e2] & 0xffffu) - bf16_bits_to_float(old8[e2] & 0xffffu);
-            float dhi = bf16_bits_to_float(a8[e2] >> 16) - bf16_bits_to_float(old8[e2] >> 16);
+            float dlo = bf16_bits_to_float(a8[e2] & 0xffffu) - bf16_bits_to_float(old8[n][e2] & 0xffffu);
+            float dhi = bf16_bits_to_float(a8[e2] >> 16) - bf16_bits_to_float(old8[n][e2] >> 16);
             if (2 * e2 >= nvalid) dlo = 0.f;
             if (2 * e2 + 1 >= nvalid) dhi = 0.f;
             d8[e2] = pack_bf16x2(dlo, dhi);
@@ -422,9 +432,31 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
     }
 
     // ---- epilogue: fp32 tile through LDS, one half of the token rows at a time ----
+    // What is added to (the cached output, or the bias of the dense form) is requested for both halves before the
+    // tile goes through LDS: the reads are in flight behind the barriers instead of one round trip per item.
     const int l32 = lane & 31;
+    constexpr int ITEMS = (BM / 2) * 32 / 256;     // 16-byte groups of four output columns per thread and half
+    static_assert((BM / 2) * 32 % 256 == 0, "the half tile must divide over the threads");
+    u32x2 old[2][ITEMS];
+#pragma unroll
+    for (int half = 0; half < 2; half++)
+#pragma unroll
+        for (int n = 0; n < ITEMS; n++) {
+            const int item = tid + n * 256;
+            const int tl = item >> 5, ch = item & 31;
+            const int tok = row0 + half * (BM / 2) + tl;
+            // one load per item whatever the case (a token past the end reads the last token's row, the dense form
+            // without a bias reads the output buffer; neither value is used): branches here would make every
+            // load wait for the one before
+            const uint16_t* src = (p.dense && p.bias)
+                                      ? p.bias + d0 + ch * 4
+                                      : p.o + ((int64_t)b * p.N + min(tok, p.N - 1)) * p.D + d0 + ch * 4;
+            old[half][n] = *reinterpret_cast<const u32x2*>(src);
+        }
+    const bool add_nothing = p.dense && !p.bias;
+#pragma unroll
     for (int half = 0; half < 2; half++) {
-        __syncthreads();
+        lds_accesses_then_barrier();
         if (wm == half) {
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
@@ -437,25 +469,21 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
                         *reinterpret_cast<float*>(smem + tl * CS + dl * 4) = acc[mt][nt][r];
                     }
         }
-        __syncthreads();
-        for (int item = tid; item < (BM / 2) * 32; item += 256) {
-            int tl = item >> 5, ch = item & 31;
-            int tok = row0 + half * (BM / 2) + tl;
-            if (tok >= p.N) continue;
+        lds_accesses_then_barrier();
+#pragma unroll
+        for (int n = 0; n < ITEMS; n++) {
+            const int item = tid + n * 256;
+            const int tl = item >> 5, ch = item & 31;
+            const int tok = row0 + half * (BM / 2) + tl;
             f32x4 a4 = *reinterpret_cast<const f32x4*>(smem + tl * CS + ch * 16);
             uint16_t* orow = p.o + ((int64_t)b * p.N + tok) * p.D + d0 + ch * 4;
-            u32x2 old = u32x2{0, 0};
-            if (p.dense) {
-                if (p.bias) old = *reinterpret_cast<const u32x2*>(p.bias + d0 + ch * 4);
-            } else {
-                old = *reinterpret_cast<const u32x2*>(orow);
-            }
-            float o0 = bf16_bits_to_float(old[0] & 0xffffu) + a4[0];
-            float o1 = bf16_bits_to_float(old[0] >> 16) + a4[1];
-            float o2 = bf16_bits_to_float(old[1] & 0xffffu) + a4[2];
-            float o3 = bf16_bits_to_float(old[1] >> 16) + a4[3];
-            u32x2 res = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
-            *reinterpret_cast<u32x2*>(orow) = res;
+            const u32x2 o2 = add_nothing ? u32x2{0, 0} : old[half][n];
+            float o0 = bf16_bits_to_float(o2[0] & 0xffffu) + a4[0];
+            float o1 = bf16_bits_to_float(o2[0] >> 16) + a4[1];
+            float o2f = bf16_bits_to_float(o2[1] & 0xffffu) + a4[2];
+            float o3 = bf16_bits_to_float(o2[1] >> 16) + a4[3];
+            u32x2 res = {pack_bf16x2(o0, o1), pack_bf16x2(o2f, o3)};
+            if (tok < p.N) *reinterpret_cast<u32x2*>(orow) = res;
         }
     }
 }
