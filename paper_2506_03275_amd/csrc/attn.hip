@@ -421,11 +421,19 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     }
 
     if (!wave_active) return;
+    // The base rows of a query block are requested together, before the block's results are stored (one round trip
+    // per block, not one per store), and without a branch: a query row that does not exist reads the chunk's last
+    // row, a call without base reads the output buffer; neither value is used.
+    const uint16_t* base_src = baseh ? baseh : outh;
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
         float ltot = st.L[qb][0];
         float f = p.o_scale / ltot;
         int qrow = (w * NQB + qb) * 16 + l16;
+        const int64_t row_off = (int64_t)(row0 + min(qrow, rows_valid - 1)) * E + 4 * g;
+        u32x2 bv[E / 16];
+#pragma unroll
+        for (int eb = 0; eb < E / 16; eb++) bv[eb] = *reinterpret_cast<const u32x2*>(base_src + row_off + eb * 16);
         if (qrow < rows_valid) {
             if (p.row_m && g == 0) {
                 p.row_m[bh * p.N + row0 + qrow] = st.m[qb] * (p.sl2 * 0.6931471805599453f);
@@ -433,14 +441,13 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             }
 #pragma unroll
             for (int eb = 0; eb < E / 16; eb++) {
-                int64_t off = (int64_t)(row0 + qrow) * E + eb * 16 + 4 * g;
-                u32x2 b = baseh ? *reinterpret_cast<const u32x2*>(baseh + off) : u32x2{0, 0};
+                u32x2 b = baseh ? bv[eb] : u32x2{0, 0};
                 float o0 = bf16_bits_to_float(b[0] & 0xffffu) + f * st.O[eb][qb][0];
                 float o1 = bf16_bits_to_float(b[0] >> 16) + f * st.O[eb][qb][1];
                 float o2 = bf16_bits_to_float(b[1] & 0xffffu) + f * st.O[eb][qb][2];
                 float o3 = bf16_bits_to_float(b[1] >> 16) + f * st.O[eb][qb][3];
                 u32x2 r2 = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
-                *reinterpret_cast<u32x2*>(outh + off) = r2;
+                *reinterpret_cast<u32x2*>(outh + row_off + eb * 16) = r2;
             }
         }
     }
