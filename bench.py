@@ -410,6 +410,10 @@ def ceilings_bench(dev):
     src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
     dst = torch.empty_like(src)
     nbytes = src.numel() * 4
+    out["lds_fill_GBps"] = {}                          # the GEMM kernels' tile-loading pattern without arithmetic
+    for label, rows in (("rows_from_1.5MB_in_L2", 256), ("rows_from_100MB_beyond_L2", 16384)):
+        ms = timed(lambda: cl.lds_fill(src, rows, 480, sink))
+        out["lds_fill_GBps"][label] = round(cl.lds_fill_bytes(480) / (ms * 1e-3) / 1e9, 1)
     out["read_GBps"] = round(nbytes / (timed(lambda: cl.read(src, sink), 5) * 1e-3) / 1e9, 1)
     out["copy_GBps_read_plus_write"] = round(2 * nbytes / (timed(lambda: cl.copy(src, dst), 5) * 1e-3) / 1e9, 1)
     assert torch.equal(dst[:4096], src[:4096]) and torch.equal(dst[-4096:], src[-4096:])

@@ -40,6 +40,14 @@ double chipmunk_probe_mfma_slots_flops(int blocks_per_cu, int iters);
 int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int head_dim, int iters, float* sink,
                                   void* stream);
 
+/* The tile-loading pattern of the GEMM kernels without arithmetic: 8 workgroups per compute unit in all, two
+ * resident at a time, each running `steps` double-buffered steps of 40 KB of asynchronous 16-byte transfers to LDS
+ * (320 pieces of 128 bytes, one per row of 6144 bytes; rows hashed over the first `rows` rows of src, which must
+ * hold rows * 6144 bytes).  A small `rows` keeps the source in L2, a large one sends every piece beyond it.
+ * chipmunk_probe_lds_fill_bytes gives the bytes one launch moves.  sink: 8 * 256 * (compute units) floats. */
+double chipmunk_probe_lds_fill_bytes(int steps);
+int32_t chipmunk_probe_lds_fill(const void* src, size_t src_bytes, uint32_t rows, int steps, float* sink, void* stream);
+
 /* Reads `bytes` (multiple of 16) once with 16-byte loads, eight in flight per lane. */
 int32_t chipmunk_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 

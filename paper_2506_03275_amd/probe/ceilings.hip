@@ -136,6 +136,43 @@ __global__ __launch_bounds__(256) void mfma_slot_kernel(float* sink, int iters) 
     sink[blockIdx.x * 256 + threadIdx.x] = sum;
 }
 
+// The tile-loading pattern of the GEMM kernels with no arithmetic: 4 waves, each of which requests ten wave-wide
+// 16-byte asynchronous transfers to LDS per step (40 KB per workgroup and step: 320 pieces of 128 bytes, one per row,
+// rows of 6144 bytes picked by a hash of the workgroup and slot from the first `rows` rows of src), double buffered
+// exactly like the kernels: wait for the step in flight, barrier, request the next one, read a word of the current one.
+__global__ __launch_bounds__(256) void lds_fill_kernel(const uint8_t* __restrict__ src, uint32_t rows, int steps, float* sink) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t fill_smem[];
+    constexpr int kLoads = 10, kStage = kLoads * 4096;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    uint32_t off[kLoads];
+    for (int i = 0; i < kLoads; i++) {
+        uint32_t row = ((blockIdx.x * 977u + (i * 4 + w) * 8 + (lane >> 3)) * 2654435761u >> 8) % rows;
+        off[i] = row * 6144u + (lane & 7) * 16;
+    }
+    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)fill_smem + w * 1024));
+    const uint64_t base = reinterpret_cast<uint64_t>(src);
+    auto request = [&](int piece, int stage) {
+        const uint64_t b = base + (uint64_t)piece * 128;
+        const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                            (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+        for (int i = 0; i < kLoads; i++)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds0 + stage * kStage + i * 4096), "v"(off[i]), "s"(ub)
+                         : "memory");
+    };
+    float acc = 0.f;
+    request(0, 0);
+    for (int kt = 0; kt < steps; kt++) {
+        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+        __builtin_amdgcn_s_barrier();
+        request((kt + 1) % 48, (kt + 1) & 1);
+        acc += *reinterpret_cast<const float*>(fill_smem + (kt & 1) * kStage + tid * 16);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+    sink[blockIdx.x * 256 + tid] = acc;
+}
+
 __global__ __launch_bounds__(256) void read_kernel(const float4* __restrict__ x, size_t n4, float* sink) {
     constexpr int U = 8;
     const size_t stride = (size_t)gridDim.x * 256 * U;
@@ -250,6 +287,29 @@ extern "C" int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int h
         else if (every == 1) hipLaunchKernelGGL((mfma_slot_kernel<16, 1>), grid, block, 0, s, sink, iters);
         else hipLaunchKernelGGL((mfma_slot_kernel<16, 2>), grid, block, 0, s, sink, iters);
     }
+    return status();
+}
+
+extern "C" double chipmunk_probe_lds_fill_bytes(int steps) {
+    if (steps < 1) return 0.0;
+    return 40960.0 * steps * 8.0 * (double)compute_units();
+}
+
+extern "C" int32_t chipmunk_probe_lds_fill(const void* src, size_t src_bytes, uint32_t rows, int steps, float* sink,
+                                           void* stream) {
+    if (!src || !sink || steps < 1 || rows < 1 || rows > (1u << 20)) return -1;
+    if (src_bytes < (size_t)rows * 6144 || (reinterpret_cast<uintptr_t>(src) & 15)) return -1;
+    const int cus = compute_units();
+    if (cus < 1) return -6;
+    constexpr int lds = 2 * 10 * 4096;   // two workgroups per compute unit, as in the GEMM kernels
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)lds_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return -6;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(lds_fill_kernel, dim3((unsigned)(cus * 8)), dim3(256), lds, (hipStream_t)stream,
+                       (const uint8_t*)src, rows, steps, sink);
     return status();
 }
 

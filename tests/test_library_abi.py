@@ -93,7 +93,7 @@ def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
     text = open(os.path.join(ROOT, "paper_2506_03275_amd", "probe", "ceilings.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = sorted(set(re.findall(r"\b(chipmunk_probe_[a-z0-9_]+)\s*\(", text)))
-    assert len(declared) == 7
+    assert len(declared) == 9
     for name in declared:
         assert hasattr(lib, name)
     P = ctypes.c_void_p
@@ -106,5 +106,7 @@ def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
     assert lib.chipmunk_probe_mfma_slots(16, 1, 1, 10, a, None) == -1     # head dimension of the vector mix
     assert lib.chipmunk_probe_mfma_phases(5, 1, 10, a, None) == -1         # phase length
     assert lib.chipmunk_probe_mfma_slots_flops(1, 0) == 0.0
+    assert lib.chipmunk_probe_lds_fill(a, 6144, 2, 10, a, None) == -1     # src smaller than rows * 6144
+    assert lib.chipmunk_probe_lds_fill_bytes(0) == 0.0
     assert lib.chipmunk_probe_read(a, 24, a, None) == -1                  # bytes % 16
     assert lib.chipmunk_probe_copy(a, P(0x2008), 64, None) == -1          # alignment
