@@ -47,7 +47,7 @@ __device__ __forceinline__ float gelu(float x, int act) {
     if (act == CHIPMUNK_ACT_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
     // tanh form: 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
     float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x / (1.f + __builtin_amdgcn_exp2f(-2.885390081777927f * u));
+    return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-2.885390081777927f * u));  // v_rcp_f32: 1 ulp, the result is rounded to bf16
 }
 
 struct Gemm1Params {
