@@ -377,12 +377,12 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     };
 
     // The query loads must not be left pending into the loop: a wait for them inside
-    // the loop would also wait for every tile transfer in flight.
+    // the loop would also wait for every tile transfer in flight.  The columns of the
+    // first step are requested beside them: one round trip for both.
+    load_cols(0);
     wait_all_memory();
 
     // first step in flight; columns of the second step requested
-    load_cols(0);
-    wait_all_memory();
     gather(0);
     load_cols(kTilesPerStep);
 
