@@ -110,3 +110,13 @@ def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
     assert lib.chipmunk_probe_lds_fill_bytes(0) == 0.0
     assert lib.chipmunk_probe_read(a, 24, a, None) == -1                  # bytes % 16
     assert lib.chipmunk_probe_copy(a, P(0x2008), 64, None) == -1          # alignment
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits (no GPU is touched on the way)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
