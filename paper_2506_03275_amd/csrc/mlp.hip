@@ -42,6 +42,28 @@ __device__ __forceinline__ bool xcd_tile_of_block(int col_tiles, int units, int*
 }
 static int xcd_grid_size(int col_tiles, int units) { return ((units + 7) / 8) * 8 * col_tiles; }
 
+// The dense forms (every neuron selected) share the weight tiles between chunks as well, and a weight tile is as
+// large as a chunk's rows: here 8 chunks x 8 column tiles of one XCD are mapped to 64 consecutive slots, so that what
+// runs side by side on an XCD reads 8 weight tiles and 8 row tiles, each eight times, instead of 64 weight tiles once.
+// Chunks and column tiles are padded to multiples of 8 per XCD; padding ids return false.
+__device__ __forceinline__ bool xcd_tile_of_block_grouped(int col_tiles, int units, int* unit, int* col_tile) {
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int ctb_count = (col_tiles + 7) >> 3;          // blocks of 8 column tiles
+    const int ct8 = slot & 7, lc8 = (slot >> 3) & 7;
+    const int rest = slot >> 6;                          // = group of 8 local chunks * ctb_count + column-tile block
+    const int g = rest / ctb_count, ctb = rest - g * ctb_count;
+    const int u = (g * 8 + lc8) * 8 + xcd;               // local chunk g*8+lc8 of this XCD
+    const int ct = ctb * 8 + ct8;
+    *unit = u;
+    *col_tile = ct;
+    return u < units && ct < col_tiles;
+}
+static int xcd_grid_size_grouped(int col_tiles, int units) {
+    const int local = (units + 7) / 8;                   // chunks per XCD
+    return ((local + 7) / 8) * ((col_tiles + 7) / 8) * 64 * 8;
+}
+
 
 __device__ __forceinline__ float gelu(float x, int act) {
     if (act == CHIPMUNK_ACT_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
@@ -88,7 +110,8 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
         col_tile = blockIdx.x % p.col_tiles;
         unit = (blockIdx.x / p.col_tiles) % p.units;
         piece = blockIdx.x / (p.col_tiles * p.units);
-    } else if (!xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile)) {
+    } else if (MODE == kDenseAct ? !xcd_tile_of_block_grouped(p.col_tiles, p.units, &unit, &col_tile)
+                                 : !xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile)) {
         return;
     }
     const int b = unit / p.NB, chunk = unit % p.NB;
@@ -311,7 +334,9 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
     const int l16 = lane & 15, mb = (lane >> 4) & 1, h = lane >> 5;
 
     int unit, col_tile;
-    if (!xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile)) return;
+    if (p.dense ? !xcd_tile_of_block_grouped(p.col_tiles, p.units, &unit, &col_tile)
+                : !xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile))
+        return;
     const int b = unit / p.NB, chunk = unit % p.NB;
     const int row0 = chunk * BM;
     const int d0 = col_tile * kBN;
@@ -556,7 +581,9 @@ static int32_t launch_gemm1(Gemm1Params p, int col_tiles, int units, hipStream_t
             return CHIPMUNK_ERR_LAUNCH;
         attr_set = true;
     }
-    const int grid = MODE == kPlainF32 ? col_tiles * units * p.ksplit : xcd_grid_size(col_tiles, units);
+    const int grid = MODE == kPlainF32 ? col_tiles * units * p.ksplit
+                     : MODE == kDenseAct ? xcd_grid_size_grouped(col_tiles, units)
+                                         : xcd_grid_size(col_tiles, units);
     hipLaunchKernelGGL((mlp_gemm1_kernel<BM, MODE>), dim3(grid), dim3(256), lds, s, p);
     return launch_status();
 }
@@ -575,7 +602,8 @@ static int32_t launch_gemm2(Gemm2Params p, int col_tiles, int units, hipStream_t
             return CHIPMUNK_ERR_LAUNCH;
         attr_set = true;
     }
-    hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3(xcd_grid_size(col_tiles, units)), dim3(256), lds, s, p);
+    const int grid = p.dense ? xcd_grid_size_grouped(col_tiles, units) : xcd_grid_size(col_tiles, units);
+    hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3((unsigned)grid), dim3(256), lds, s, p);
     return launch_status();
 }
 
