@@ -23,6 +23,7 @@ paper's 9.3x kernel figure is for this sequence length).
 prints ONE JSON line.  Nothing here runs on more than one GPU.
 """
 import argparse
+import hashlib
 import json
 import math
 import os
@@ -45,11 +46,30 @@ CALIBRATION_COPY_BYTES = 256 << 20
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE), each counter scaled by what it
 # read for the --traffic-calibration copy of known size; the summaries with the commands are
 # profiles/attn_sparse_delta_traffic_<workload>.txt.  A counter run cannot happen inside this
-# process, so the figure is carried here and reported with the live timing.
+# process, so the figure is carried here and reported with the live timing, but only while the
+# attention kernel's sources are the ones the counters were taken on (ATTN_SOURCES_MEASURED is the
+# digest attn_sources_digest() gave then); after any change to them `traffic` is null until the
+# counters are taken again.
+ATTN_SOURCES_MEASURED = "unmeasured"
 MEASURED_ATTN_TRAFFIC_BYTES = {
     "flux": 2.0 * 67358 * 1024 + 1.0 * 28830 * 1024,
     "hunyuan": 2.0 * 12620292 * 1024 + 1.0 * 721739 * 1024,
 }
+
+
+def attn_sources_digest():
+    """Digest of the sources the attention kernel is built from."""
+    h = hashlib.sha256()
+    for rel in ("paper_2506_03275_amd/csrc/attn.hip", "paper_2506_03275_amd/csrc/common.h"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_attn_traffic(workload, default_sparsity):
+    if not default_sparsity or attn_sources_digest() != ATTN_SOURCES_MEASURED:
+        return None
+    return MEASURED_ATTN_TRAFFIC_BYTES.get(workload)
 
 WORKLOAD_TEXT = {
     "tiny": "Tiny: 1024 tokens (8x8x16 grid), 2 heads x 64, MLP 256->1024, chunk 128, keep 25%",
@@ -110,6 +130,10 @@ def build_state(cm, name, attn_keep, mlp_keep, seed, dev):
 
     w1, b1, w2, b2 = si.mlp_weights(D, F, seed, dev)
     x1, x2 = si.mlp_steps(B, N, D, seed, dev)
+    # The MLP caches are updated in place, so a step repeated on the same input would find a_cache already equal
+    # to its activations and multiply an all-zero delta in GEMM2.  Consecutive timed steps therefore alternate
+    # between two inputs that differ like consecutive diffusion steps do: every step sees a non-zero delta.
+    x3 = si.perturb_all(x2, si.generator(seed + 2000004, dev))
     a_cache = torch.zeros((B, F, -(-N // 8) * 8), dtype=torch.bfloat16, device=dev)
     m_cache = torch.empty_like(x1)
     cm.mlp_dense(x1, w1, b1, w2, b2, m_cache, a_cache, c, st["act"])
@@ -122,13 +146,16 @@ def build_state(cm, name, attn_keep, mlp_keep, seed, dev):
     perm = torch.empty((N,), dtype=torch.int32, device=dev)
     npre, (gt, gh, gw), nsuf, (vt, vh, vw) = cfg["n_prefix"], cfg["grid"], cfg["n_suffix"], cfg["voxel"]
     cm.voxel_reorder(None, None, perm, None, npre, gt, gh, gw, nsuf, vt, vh, vw)
-    x_raster = torch.empty_like(x2)
-    cm.voxel_reorder(x2, x_raster, None, None, npre, gt, gh, gw, nsuf, vt, vh, vw, inverse=True)
+    x_rasters = []
+    for xs in (x2, x3):
+        x_raster = torch.empty_like(xs)
+        cm.voxel_reorder(xs, x_raster, None, None, npre, gt, gh, gw, nsuf, vt, vh, vw, inverse=True)
+        x_rasters.append(x_raster)
     torch.cuda.synchronize()
 
     st.update(q=q2, k=k2, v=v2, colsum=colsum, ld=ld, idx_a=idx_a, cnt_a=cnt_a, o_cache_attn=o_cache_attn,
-              o_attn=torch.empty_like(q2), w1=w1, b1=b1, w2=w2, b2=b2, x_raster=x_raster, x=torch.empty_like(x2),
-              x_expect=x2, a_cache=a_cache, m_cache=m_cache, T_m=T_m, T=torch.empty_like(T_m), ws_tm=ws_tm,
+              o_attn=torch.empty_like(q2), w1=w1, b1=b1, w2=w2, b2=b2, x_rasters=x_rasters, x=torch.empty_like(x2),
+              x_expects=[x2, x3], step_count=0, a_cache=a_cache, m_cache=m_cache, T_m=T_m, T=torch.empty_like(T_m), ws_tm=ws_tm,
               idx_m=torch.zeros((B, NB, max(k_m, 1)), dtype=torch.int32, device=dev),
               cnt_m=torch.zeros((B, NB), dtype=torch.int32, device=dev),
               ws_mlp=u8(cm.mlp_workspace_bytes(B, N, D, F, c, max(k_m, 1))))
@@ -152,8 +179,10 @@ def sparse_step(cm, st, timer=None):
         fn()
         b.record()
 
-    stage("voxel_reorder", lambda: cm.voxel_reorder(st["x_raster"], st["x"], None, None, npre, gt, gh, gw, nsuf,
-                                                    vt, vh, vw))
+    which = st["step_count"] & 1                 # alternate between the two step inputs (see build_state)
+    st["step_count"] += 1
+    stage("voxel_reorder", lambda: cm.voxel_reorder(st["x_rasters"][which], st["x"], None, None, npre, gt, gh, gw,
+                                                    nsuf, vt, vh, vw))
     stage("topk_attn", lambda: lib.chipmunk_topk_cols(st["colsum"].data_ptr(), None, B * H * NB, N, st["ld"],
                                                       st["k_a"], st["idx_a"].data_ptr(), st["cnt_a"].data_ptr(),
                                                       st["idx_a"].shape[-1], stream))
@@ -357,7 +386,7 @@ def stack_bench(cm, args, steps, warmup, dev):
                            "pre-generated, so overlapping the NEXT block's index work is a property of this stack"},
         "roofline": {"kernel": "attn_sparse_delta_kernel", "bound": "mfma", "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES["hunyuan"] if args.attn_keep is None else None,
+                     "traffic": measured_attn_traffic("hunyuan", args.attn_keep is None),
                      "launch_ms": attn_ms, "algorithmic_flops_per_launch": fl_attn},
         "stack": {"sparse_pass_ms_side_stream": overlap_ms, "sparse_pass_ms_serial": serial_ms,
                   "side_stream_gain": serial_ms / overlap_ms, "dense_step_ms_4_blocks": dense_ms,
@@ -368,12 +397,11 @@ def stack_bench(cm, args, steps, warmup, dev):
 
 
 def ceilings_bench(dev):
-    """What the device sustains for bare bf16 MFMA streams (alone, and alternating with fp32 vector work as a
-    softmax between two GEMMs does) and for streaming reads and copies: context for the roofline fractions."""
+    """What the device sustains for bare bf16 MFMA streams and for streaming reads and copies: the measured
+    ceilings the roofline fractions are also quoted against."""
     from paper_2506_03275_amd import ceilings as cl
     sink = torch.zeros(1 << 20, dtype=torch.float32, device=dev)
-    out = {"mfma_bf16_tflops": {}, "unit_note": "valu = fp32 FMAs per 393216 flop of MFMAs, in a phase of their own; "
-           "waves = waves per SIMD"}
+    out = {"mfma_bf16_tflops": {}, "unit_note": "waves = waves per SIMD"}
 
     def timed(fn, reps=3):
         best = None
@@ -390,30 +418,12 @@ def ceilings_bench(dev):
     iters = 60000                                    # 20-40 ms per launch: long enough for the clocks to settle
     for shape in (16, 32):
         for waves in (1, 2):
-            for valu in (0, 64, 128):
-                ms = timed(lambda: cl.mfma_bf16(shape, waves, valu, iters // waves, sink))
-                name = f"{shape}x{shape}x{512 // shape}_waves{waves}_valu{valu}"
-                out["mfma_bf16_tflops"][name] = round(cl.mfma_flops(waves, iters // waves) / (ms * 1e-3) / 1e12, 1)
-    out["mfma_phase_length_tflops"] = {}               # 16x16x32, two waves per SIMD, 60 FMAs per 24 MFMAs
-    for per_phase in (24, 12, 8, 4, 2):
-        ms = timed(lambda: cl.mfma_phases(per_phase, 2, iters // 2, sink))
-        out["mfma_phase_length_tflops"][f"{per_phase}_mfmas_per_phase"] = round(
-            cl.mfma_flops(2, iters // 2) / (ms * 1e-3) / 1e12, 1)
-    out["mfma_slots_tflops"] = {}
-    for shape in (16, 32):
-        for waves in (1, 2):
-            for head_dim in (0, 64, 128):                # softmax vector work per flop of that head dimension
-                it = 30000 // waves
-                ms = timed(lambda: cl.mfma_slots(shape, waves, head_dim, it, sink))
-                name = f"{shape}x{shape}x{512 // shape}_waves{waves}_" + (f"softmax_of_head_dim_{head_dim}" if head_dim else "alone")
-                out["mfma_slots_tflops"][name] = round(cl.mfma_slots_flops(waves, it) / (ms * 1e-3) / 1e12, 1)
+            ms = timed(lambda: cl.mfma_bf16(shape, waves, iters // waves, sink))
+            name = f"{shape}x{shape}x{512 // shape}_waves{waves}"
+            out["mfma_bf16_tflops"][name] = round(cl.mfma_flops(waves, iters // waves) / (ms * 1e-3) / 1e12, 1)
     src = torch.ones(1 << 28, dtype=torch.float32, device=dev)        # 1 GiB
     dst = torch.empty_like(src)
     nbytes = src.numel() * 4
-    out["lds_fill_GBps"] = {}                          # the GEMM kernels' tile-loading pattern without arithmetic
-    for label, rows in (("rows_from_1.5MB_in_L2", 256), ("rows_from_100MB_beyond_L2", 16384)):
-        ms = timed(lambda: cl.lds_fill(src, rows, 480, sink))
-        out["lds_fill_GBps"][label] = round(cl.lds_fill_bytes(480) / (ms * 1e-3) / 1e9, 1)
     out["read_GBps"] = round(nbytes / (timed(lambda: cl.read(src, sink), 5) * 1e-3) / 1e9, 1)
     out["copy_GBps_read_plus_write"] = round(2 * nbytes / (timed(lambda: cl.copy(src, dst), 5) * 1e-3) / 1e9, 1)
     assert torch.equal(dst[:4096], src[:4096]) and torch.equal(dst[-4096:], src[-4096:])
@@ -485,7 +495,9 @@ def main():
         sparse_step(cm, st, timer)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
-    assert torch.equal(st["x"], st["x_expect"]), "voxel reorder did not restore the token order"
+    assert torch.equal(st["x"], st["x_expects"][(st["step_count"] - 1) & 1]), "voxel reorder did not restore the token order"
+    delta_rms = float(st["ws_mlp"][: 1 << 20].view(torch.bfloat16).float().pow(2).mean().sqrt())
+    assert st["k_m"] == 0 or delta_rms > 0.0, "the timed MLP steps multiplied an all-zero delta"
 
     stages = {n: timer.mean_ms(n) for n in timer.spans}
     fl_attn, fl_mlp = useful_flops(st)
@@ -496,24 +508,29 @@ def main():
     achieved = fl_attn / (attn_ms * 1e-3) / 1e12
     roofline = {"kernel": "attn_sparse_delta_kernel", "bound": "mfma", "achieved": achieved,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.workload) if args.attn_keep is None else None,
+                "traffic": measured_attn_traffic(args.workload, args.attn_keep is None),
                 "launch_ms": attn_ms, "algorithmic_flops_per_launch": fl_attn}
 
     graph_extra = None
     if args.graph:
-        # The same step as one HIP graph: no launch gaps and no per-stage events between the kernels.
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            sparse_step(cm, st)
-        for _ in range(max(warmup, 1)):
-            g.replay()
+        # The same step as one HIP graph per step input (the two inputs alternate as in the eager loop): no launch
+        # gaps and no per-stage events between the kernels.
+        graphs = []
+        for which in (0, 1):
+            st["step_count"] = which
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                sparse_step(cm, st)
+            graphs.append(g)
+        for i in range(2 * max(warmup, 1)):
+            graphs[i & 1].replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            g.replay()
+        for i in range(steps):
+            graphs[i & 1].replay()
         torch.cuda.synchronize()
         g_ms = (time.perf_counter() - t0) * 1e3 / steps
-        assert torch.equal(st["x"], st["x_expect"]), "voxel reorder did not restore the token order (graph replay)"
+        assert any(torch.equal(st["x"], e) for e in st["x_expects"]), "voxel reorder did not restore the token order (graph replay)"
         graph_extra = {"ms_per_step": g_ms, "useful_tflops": (fl_attn + fl_mlp) / (g_ms * 1e-3) / 1e12}
 
     extra = {"stage_ms": stages,

@@ -85,7 +85,10 @@ int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R, int C, in
  * int32; counts: [B,H,NB] int32, each in [0, k_stride].  idx == NULL and
  * counts == NULL selects every column 0..N-1 (dense attention on the same
  * kernel; base may then be NULL, meaning zero).
- * E in {64,128}; c in {128,192}. */
+ * E in {64,128}; c in {128,192}; N*E must stay below 2^31 elements (32-bit byte
+ * offsets of K/V rows inside one head; the same limit holds for every attention
+ * entry point below).  softmax_scale must be positive and finite, o_scale finite
+ * (both are checked on their bit patterns: a NaN is rejected, nothing is launched). */
 int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                                    const int32_t* idx, const int32_t* counts,
                                    const uint16_t* base, uint16_t* out,
@@ -122,8 +125,11 @@ int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, const uint16_t
  * an earlier step they are the paper's approximation, meant only to rank
  * columns.  q, k: [B,H,N,E] bf16; prev_m, prev_l: [B,H,N] fp32; colsum:
  * [B,H,NB,ld_colsum] fp32 (ld_colsum >= N, multiple of 4; columns N..ld-1 are
- * left untouched).  Scores far above prev_m overflow to +inf like the formula
- * does.  E in {64,128}; c in {128,192}. */
+ * left untouched).  The sums are meant for normalisers that are close to the
+ * current ones; they are exact fp32 evaluations of the formula while every
+ * weight exp(score - prev_m) / prev_l stays below 2^126.  A weight beyond that
+ * makes its column's sum +inf here (like the formula in fp32).
+ * E in {64,128}; c in {128,192}. */
 int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t* k, const float* prev_m,
                                    const float* prev_l, float* colsum, int64_t ld_colsum,
                                    int B, int H, int N, int E, int c, float softmax_scale, void* stream);
@@ -138,7 +144,15 @@ int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t* k, const f
  * prev_l.  new_m == prev_m and new_l == prev_l (update in place) is allowed:
  * the workgroup of a chunk reads the old values of its own rows, and only
  * those, before it writes the new ones; any other overlap is not.  Other
- * arguments as for chipmunk_attn_colsum_stale and chipmunk_attn_dense. */
+ * arguments as for chipmunk_attn_colsum_stale and chipmunk_attn_dense.
+ * Range: this kernel forms a weight as (probability against the running
+ * softmax reference) x (one factor per query), and caps that factor at 2^126.
+ * While the largest weight exp(score - prev_m) / prev_l of every query row
+ * stays below 2^118 the sums agree with chipmunk_attn_colsum_stale; beyond
+ * that (normalisers more than about 80 below a row's current maximum) the
+ * row's contributions are scaled down together: a column's sum is then a large
+ * finite number or +inf, never NaN, and the two entry points may order such
+ * columns differently. */
 int32_t chipmunk_attn_dense_colsum_stale(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                                          uint16_t* out, const float* prev_m, const float* prev_l,
                                          float* colsum, int64_t ld_colsum, float* new_m, float* new_l,

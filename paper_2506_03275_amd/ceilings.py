@@ -17,13 +17,7 @@ def load():
         lib = ctypes.CDLL(path)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         lib.chipmunk_probe_mfma_flops.argtypes, lib.chipmunk_probe_mfma_flops.restype = [i32, i32], ctypes.c_double
-        lib.chipmunk_probe_mfma_bf16.argtypes, lib.chipmunk_probe_mfma_bf16.restype = [i32] * 4 + [vp, vp], ctypes.c_int32
-        lib.chipmunk_probe_mfma_phases.argtypes, lib.chipmunk_probe_mfma_phases.restype = [i32] * 3 + [vp, vp], ctypes.c_int32
-        lib.chipmunk_probe_mfma_slots_flops.argtypes, lib.chipmunk_probe_mfma_slots_flops.restype = [i32, i32], ctypes.c_double
-        lib.chipmunk_probe_mfma_slots.argtypes, lib.chipmunk_probe_mfma_slots.restype = [i32] * 4 + [vp, vp], ctypes.c_int32
-        lib.chipmunk_probe_lds_fill_bytes.argtypes, lib.chipmunk_probe_lds_fill_bytes.restype = [i32], ctypes.c_double
-        lib.chipmunk_probe_lds_fill.argtypes = [vp, sz, ctypes.c_uint32, i32, vp, vp]
-        lib.chipmunk_probe_lds_fill.restype = ctypes.c_int32
+        lib.chipmunk_probe_mfma_bf16.argtypes, lib.chipmunk_probe_mfma_bf16.restype = [i32] * 3 + [vp, vp], ctypes.c_int32
         lib.chipmunk_probe_read.argtypes, lib.chipmunk_probe_read.restype = [vp, sz, vp, vp], ctypes.c_int32
         lib.chipmunk_probe_copy.argtypes, lib.chipmunk_probe_copy.restype = [vp, vp, sz, vp], ctypes.c_int32
         _LIB = lib
@@ -43,32 +37,9 @@ def mfma_flops(blocks_per_cu, iters):
     return float(load().chipmunk_probe_mfma_flops(blocks_per_cu, iters))
 
 
-def mfma_bf16(shape, blocks_per_cu, valu_ops, iters, sink):
-    _check(load().chipmunk_probe_mfma_bf16(shape, blocks_per_cu, valu_ops, iters, sink.data_ptr(), _stream()),
+def mfma_bf16(shape, blocks_per_cu, iters, sink):
+    _check(load().chipmunk_probe_mfma_bf16(shape, blocks_per_cu, iters, sink.data_ptr(), _stream()),
            "chipmunk_probe_mfma_bf16")
-
-
-def mfma_phases(mfmas_per_phase, blocks_per_cu, iters, sink):
-    _check(load().chipmunk_probe_mfma_phases(mfmas_per_phase, blocks_per_cu, iters, sink.data_ptr(), _stream()),
-           "chipmunk_probe_mfma_phases")
-
-
-def lds_fill_bytes(steps):
-    return float(load().chipmunk_probe_lds_fill_bytes(steps))
-
-
-def lds_fill(src, rows, steps, sink):
-    _check(load().chipmunk_probe_lds_fill(src.data_ptr(), src.numel() * src.element_size(), rows, steps,
-                                          sink.data_ptr(), _stream()), "chipmunk_probe_lds_fill")
-
-
-def mfma_slots_flops(blocks_per_cu, iters):
-    return float(load().chipmunk_probe_mfma_slots_flops(blocks_per_cu, iters))
-
-
-def mfma_slots(shape, blocks_per_cu, head_dim, iters, sink):
-    _check(load().chipmunk_probe_mfma_slots(shape, blocks_per_cu, int(head_dim), iters, sink.data_ptr(),
-                                            _stream()), "chipmunk_probe_mfma_slots")
 
 
 def read(src, sink):

@@ -230,12 +230,6 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
     }
 }
 
-template <int N>
-__device__ __forceinline__ void wait_vmem_at_most() {  // at most N vector-memory loads still in flight
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
 // NWAVES waves per workgroup, each owning NQB blocks of 16 queries: c = 16 * NQB * NWAVES.
 // FUSED (dense launches only: no index list): the column sums of Alg. 4 are formed from the same score tiles.
 template <int E, int NQB, int NWAVES, bool FUSED = false>
@@ -578,13 +572,11 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
 template <int E, int NQB, int NWAVES, bool FUSED = false>
 static int32_t launch_attn_variant(const AttnParams& p, int64_t units, hipStream_t s) {
     constexpr int lds = kStages * 2 * kTileRows * E * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-            return CHIPMUNK_ERR_LAUNCH;
-        attr_set = true;
-    }
+    // set at every launch: the attribute is kept per device, and a flag remembered here would be neither
+    // per device nor safe between host threads
+    if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+        return CHIPMUNK_ERR_LAUNCH;
     hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>), dim3((unsigned)units), dim3(64 * NWAVES), lds, s, p);
     return launch_status();
 }
@@ -612,6 +604,17 @@ static int32_t launch_colsum(const ColsumParams& cp, int E, int64_t units, hipSt
     return launch_status();
 }
 
+// Shape rules common to the attention entry points.  Offsets of K/V rows inside one head are 32-bit byte offsets.
+static int32_t check_attn_shapes(int B, int H, int N, int E, int c, float softmax_scale) {
+    if (B < 1 || H < 1 || N < 1) return CHIPMUNK_ERR_SHAPE;
+    if (!is_positive_finite_scalar(softmax_scale)) return CHIPMUNK_ERR_SHAPE;
+    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if ((int64_t)N * E * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    if ((int64_t)B * H * ((N + c - 1) / c) > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
+    return CHIPMUNK_OK;
+}
+
 }  // namespace chipmunk
 
 using namespace chipmunk;
@@ -624,16 +627,13 @@ extern "C" int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t*
     if (!q || !k || !v || !out) return CHIPMUNK_ERR_NULL;
     if ((idx == nullptr) != (counts == nullptr)) return CHIPMUNK_ERR_NULL;
     if (idx && !base) return CHIPMUNK_ERR_NULL;
-    if (B < 1 || H < 1 || N < 1 || k_stride < 0) return CHIPMUNK_ERR_SHAPE;
-    if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY) || !(o_scale == o_scale)) return CHIPMUNK_ERR_SHAPE;
-    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
-    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (k_stride < 0 || !is_finite_scalar(o_scale)) return CHIPMUNK_ERR_SHAPE;
+    if (int32_t st = check_attn_shapes(B, H, N, E, c, softmax_scale)) return st;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(base) ||
         !aligned16(idx) || !aligned16(counts))
         return CHIPMUNK_ERR_ALIGN;
     int NB = (N + c - 1) / c;
     int64_t units = (int64_t)B * H * NB;
-    if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
     AttnParams p;
     p.q = q; p.k = k; p.v = v; p.base = base; p.out = out; p.idx = idx; p.counts = counts;
     p.row_m = nullptr; p.row_l = nullptr;
@@ -653,10 +653,7 @@ extern "C" int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, con
                                        float* colsum, int64_t ld_colsum, int B, int H, int N, int E, int c,
                                        float softmax_scale, void* ws, size_t ws_bytes, void* stream) {
     if (!q || !k || !v || !out) return CHIPMUNK_ERR_NULL;
-    if (B < 1 || H < 1 || N < 1) return CHIPMUNK_ERR_SHAPE;
-    if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return CHIPMUNK_ERR_SHAPE;
-    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
-    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (int32_t st = check_attn_shapes(B, H, N, E, c, softmax_scale)) return st;
     if (colsum && ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(colsum) || !aligned16(ws) ||
         (colsum && (ld_colsum % 4) != 0))
@@ -664,7 +661,6 @@ extern "C" int32_t chipmunk_attn_dense(const uint16_t* q, const uint16_t* k, con
     if (colsum && (!ws || ws_bytes < chipmunk_attn_dense_workspace_bytes(B, H, N))) return CHIPMUNK_ERR_WORKSPACE;
     int NB = (N + c - 1) / c;
     int64_t units = (int64_t)B * H * NB;
-    if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
     hipStream_t s = (hipStream_t)stream;
     AttnParams p;
     p.q = q; p.k = k; p.v = v; p.base = nullptr; p.out = out; p.idx = nullptr; p.counts = nullptr;
@@ -686,16 +682,13 @@ extern "C" int32_t chipmunk_attn_colsum_stale(const uint16_t* q, const uint16_t*
                                               const float* prev_l, float* colsum, int64_t ld_colsum, int B, int H,
                                               int N, int E, int c, float softmax_scale, void* stream) {
     if (!q || !k || !prev_m || !prev_l || !colsum) return CHIPMUNK_ERR_NULL;
-    if (B < 1 || H < 1 || N < 1 || ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
-    if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return CHIPMUNK_ERR_SHAPE;
-    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
-    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (int32_t st = check_attn_shapes(B, H, N, E, c, softmax_scale)) return st;
+    if (ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(colsum) || (ld_colsum % 4) != 0 ||
         (reinterpret_cast<uintptr_t>(prev_m) & 3u) || (reinterpret_cast<uintptr_t>(prev_l) & 3u))
         return CHIPMUNK_ERR_ALIGN;
     int NB = (N + c - 1) / c;
     int64_t units = (int64_t)B * H * NB;
-    if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
     ColsumParams cp;
     cp.q = q; cp.k = k; cp.row_m = prev_m; cp.row_l = prev_l; cp.colsum = colsum; cp.ld = ld_colsum;
     cp.N = N; cp.NB = NB; cp.c = c; cp.sl2 = softmax_scale * 1.4426950408889634f;
@@ -709,17 +702,14 @@ extern "C" int32_t chipmunk_attn_dense_colsum_stale(const uint16_t* q, const uin
                                                     void* stream) {
     if (!q || !k || !v || !out || !prev_m || !prev_l || !colsum) return CHIPMUNK_ERR_NULL;
     if ((new_m == nullptr) != (new_l == nullptr)) return CHIPMUNK_ERR_NULL;
-    if (B < 1 || H < 1 || N < 1 || ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
-    if (!(softmax_scale > 0.f) || !(softmax_scale < INFINITY)) return CHIPMUNK_ERR_SHAPE;
-    if (E != 64 && E != 128) return CHIPMUNK_ERR_UNSUPPORTED;
-    if (c != 128 && c != 192) return CHIPMUNK_ERR_UNSUPPORTED;
+    if (int32_t st = check_attn_shapes(B, H, N, E, c, softmax_scale)) return st;
+    if (ld_colsum < N) return CHIPMUNK_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(colsum) || (ld_colsum % 4) != 0)
         return CHIPMUNK_ERR_ALIGN;
     for (const float* f : {prev_m, prev_l, (const float*)new_m, (const float*)new_l})
         if (reinterpret_cast<uintptr_t>(f) & 3u) return CHIPMUNK_ERR_ALIGN;
     int NB = (N + c - 1) / c;
     int64_t units = (int64_t)B * H * NB;
-    if (units > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
     AttnParams p;
     p.q = q; p.k = k; p.v = v; p.base = nullptr; p.out = out; p.idx = nullptr; p.counts = nullptr;
     p.row_m = new_m; p.row_l = new_l;

@@ -98,6 +98,19 @@ __device__ __forceinline__ void lds_accesses_then_barrier() {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Scalar arguments are classified on their bit patterns: these files are compiled without NaN semantics
+// (-fno-honor-nans also covers the host half), so a comparison may be folded as if NaN did not exist.
+inline uint32_t float_bits(float x) {
+    uint32_t u;
+    __builtin_memcpy(&u, &x, sizeof u);
+    return u;
+}
+inline bool is_finite_scalar(float x) { return (float_bits(x) & 0x7f800000u) != 0x7f800000u; }
+inline bool is_positive_finite_scalar(float x) {
+    const uint32_t u = float_bits(x);
+    return (u >> 31) == 0 && u != 0 && (u & 0x7f800000u) != 0x7f800000u;
+}
+
 inline int32_t launch_status() {
     return hipGetLastError() == hipSuccess ? CHIPMUNK_OK : CHIPMUNK_ERR_LAUNCH;
 }

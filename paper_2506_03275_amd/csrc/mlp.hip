@@ -520,10 +520,11 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
 __global__ __launch_bounds__(256) void chunk_mean_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ xm,
                                                          int N, int NB, int D, int c) {
     __shared__ float s_part[3][64][8];
-    const int unit = blockIdx.y;
+    const int col_blocks = (D / 8 + 63) / 64;        // grid.x = units * col_blocks
+    const int unit = blockIdx.x / col_blocks;
     const int b = unit / NB, chunk = unit % NB;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int col8 = blockIdx.x * 64 + lane;
+    const int col8 = (blockIdx.x % col_blocks) * 64 + lane;
     const bool live = col8 * 8 < D;
     const int r0 = chunk * c, r1 = min(N, r0 + c);
     float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -574,13 +575,10 @@ static int32_t launch_gemm1(Gemm1Params p, int col_tiles, int units, hipStream_t
     p.col_tiles = col_tiles;
     p.units = units;
     constexpr int lds = 2 * (BM * 128 + kBN * 128);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)mlp_gemm1_kernel<BM, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lds) != hipSuccess)
-            return CHIPMUNK_ERR_LAUNCH;
-        attr_set = true;
-    }
+    // set at every launch: the attribute is kept per device (a flag remembered here would not be)
+    if (hipFuncSetAttribute((const void*)mlp_gemm1_kernel<BM, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+        hipSuccess)
+        return CHIPMUNK_ERR_LAUNCH;
     const int grid = MODE == kPlainF32 ? col_tiles * units * p.ksplit
                      : MODE == kDenseAct ? xcd_grid_size_grouped(col_tiles, units)
                                          : xcd_grid_size(col_tiles, units);
@@ -595,13 +593,9 @@ static int32_t launch_gemm2(Gemm2Params p, int col_tiles, int units, hipStream_t
     constexpr int stage = kBK * BM * 2 + kBK * 256;
     constexpr int epi = (BM / 2) * (128 * 4 + 32);
     constexpr int lds = 2 * stage > epi ? 2 * stage : epi;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)mlp_gemm2_kernel<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-            hipSuccess)
-            return CHIPMUNK_ERR_LAUNCH;
-        attr_set = true;
-    }
+    if (hipFuncSetAttribute((const void*)mlp_gemm2_kernel<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+        hipSuccess)
+        return CHIPMUNK_ERR_LAUNCH;
     const int grid = p.dense ? xcd_grid_size_grouped(col_tiles, units) : xcd_grid_size(col_tiles, units);
     hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3((unsigned)grid), dim3(256), lds, s, p);
     return launch_status();
@@ -636,15 +630,22 @@ static int tile_mean_pieces(int units, int F) {
     return pieces;
 }
 
+// Workspace of the token-merged pre-activation with the contraction cut in `pieces`: the chunk means in split
+// precision [units, 2 D] bf16 (rounded up to 256 bytes), then, with more than one piece, the pieces' partial
+// results [pieces, units, F] fp32.  0 when the shapes are out of range.
+static size_t tile_mean_bytes(int B, int N, int D, int F, int c, int pieces) {
+    if (check_mlp_shapes(B, N, D, F, c) != CHIPMUNK_OK) return 0;
+    const int64_t units = (int64_t)B * ((N + c - 1) / c);
+    if (units > 0x7fffff || units * 2 * D * 2 >= (1LL << 32)) return 0;
+    const size_t means = ((size_t)units * 2 * D * 2 + 255) / 256 * 256;
+    return means + (pieces > 1 ? (size_t)pieces * units * F * sizeof(float) : 0);
+}
+
 extern "C" size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, int F, int c) {
-    if (B < 1 || N < 1 || D < 1 || F < 1 || (c != 128 && c != 192)) return 0;
-    int64_t units = (int64_t)B * ((N + c - 1) / c);
+    if (check_mlp_shapes(B, N, D, F, c) != CHIPMUNK_OK) return 0;
+    const int64_t units = (int64_t)B * ((N + c - 1) / c);
     if (units > 0x7fffff) return 0;
-    size_t means = (size_t)(units * 2 * (int64_t)D * 2);
-    means = (means + 255) / 256 * 256;
-    int pieces = tile_mean_pieces((int)units, F);
-    size_t partial = pieces > 1 ? (size_t)pieces * units * F * sizeof(float) : 0;
-    return means + partial;
+    return tile_mean_bytes(B, N, D, F, c, tile_mean_pieces((int)units, F));
 }
 
 extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
@@ -713,21 +714,14 @@ extern "C" int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, con
     return c == 192 ? launch_gemm2<192>(g2, D / kBN, units, s) : launch_gemm2<128>(g2, D / kBN, units, s);
 }
 
-extern "C" int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16_t* w1, float* T, int B, int N,
-                                                 int D, int F, int c, void* ws, size_t ws_bytes, void* stream) {
-    if (!x || !w1 || !T) return CHIPMUNK_ERR_NULL;
-    int32_t st = check_mlp_shapes(B, N, D, F, c);
-    if (st != CHIPMUNK_OK) return st;
-    if (!aligned16(x) || !aligned16(w1) || !aligned16(T) || !aligned16(ws)) return CHIPMUNK_ERR_ALIGN;
-    size_t need = chipmunk_mlp_tile_mean_workspace_bytes(B, N, D, F, c);
-    if (!ws || need == 0 || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
+// chunk means -> scores GEMM (-> sum of the pieces); ws holds tile_mean_bytes(..., pieces) bytes
+static int32_t run_tile_mean(const uint16_t* x, const uint16_t* w1, float* T, int B, int N, int D, int F, int c,
+                             void* ws, int pieces, hipStream_t s) {
     const int NB = (N + c - 1) / c, units = B * NB;
-    if ((int64_t)units * 2 * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
-    hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(chunk_mean_kernel, dim3((D / 8 + 63) / 64, units), dim3(256), 0, s, x, (uint16_t*)ws, N, NB, D, c);
+    hipLaunchKernelGGL(chunk_mean_kernel, dim3((unsigned)(((D / 8 + 63) / 64) * units)), dim3(256), 0, s, x, (uint16_t*)ws,
+                       N, NB, D, c);
     if (launch_status() != CHIPMUNK_OK) return CHIPMUNK_ERR_LAUNCH;
     // scores[unit, f] = <[hi | lo](unit), [w1_f | w1_f]>: a plain GEMM with "tokens" = units
-    const int pieces = tile_mean_pieces(units, F);
     size_t means = ((size_t)units * 2 * D * 2 + 255) / 256 * 256;
     float* partial = pieces > 1 ? (float*)((char*)ws + means) : T;
     Gemm1Params g1;
@@ -735,9 +729,23 @@ extern "C" int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16
     g1.a_cache = nullptr; g1.delta_t = nullptr; g1.out_f32 = partial; g1.a_ld = 0;
     g1.N = units; g1.NB = (units + 127) / 128; g1.D = D; g1.F = F; g1.K = 2 * D; g1.ldx = 2 * D;
     g1.k_stride = F; g1.k_pad = F; g1.act = 0; g1.ksplit = pieces;
-    st = launch_gemm1<128, kPlainF32>(g1, (F + kBN - 1) / kBN, g1.NB, s);
+    int32_t st = launch_gemm1<128, kPlainF32>(g1, (F + kBN - 1) / kBN, g1.NB, s);
     if (st != CHIPMUNK_OK || pieces == 1) return st;
     int64_t n4 = (int64_t)units * F / 4;
     hipLaunchKernelGGL(sum_pieces_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, partial, T, n4, pieces);
     return launch_status();
+}
+
+extern "C" int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16_t* w1, float* T, int B, int N,
+                                                 int D, int F, int c, void* ws, size_t ws_bytes, void* stream) {
+    if (!x || !w1 || !T) return CHIPMUNK_ERR_NULL;
+    int32_t st = check_mlp_shapes(B, N, D, F, c);
+    if (st != CHIPMUNK_OK) return st;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(T) || !aligned16(ws)) return CHIPMUNK_ERR_ALIGN;
+    const int64_t units = (int64_t)B * ((N + c - 1) / c);
+    if (units > 0x7fffff || units * 2 * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    const int pieces = tile_mean_pieces((int)units, F);
+    size_t need = tile_mean_bytes(B, N, D, F, c, pieces);
+    if (!ws || need == 0 || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
+    return run_tile_mean(x, w1, T, B, N, D, F, c, ws, pieces, (hipStream_t)stream);
 }

@@ -19,158 +19,33 @@ __device__ __forceinline__ void probe_operands(bf16x8& a, bf16x8& b) {
     }
 }
 
-template <int NV>
-__device__ __forceinline__ void probe_valu(float (&v)[8]) {
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NV; j++) v[j & 7] = __builtin_fmaf(v[j & 7], 1.0001f, 0.5f);
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-template <int NV>
 __global__ __launch_bounds__(256) void mfma16_kernel(float* sink, int iters) {
     bf16x8 a, b;
     probe_operands(a, b);
     f32x4 acc[24];
     for (int i = 0; i < 24; i++) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float v[8];
-    for (int i = 0; i < 8; i++) v[i] = threadIdx.x * 0.001f + i;
     for (int it = 0; it < iters; it++) {
 #pragma unroll
         for (int i = 0; i < 24; i++) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
-        if (NV > 0) probe_valu<NV>(v);
     }
     float s = 0.f;
     for (int i = 0; i < 24; i++) s += acc[i][0] + acc[i][3];
-    for (int i = 0; i < 8; i++) s += v[i];
     sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-template <int NV>
 __global__ __launch_bounds__(256) void mfma32_kernel(float* sink, int iters) {
     bf16x8 a, b;
     probe_operands(a, b);
     f32x16 acc[12];
     for (int i = 0; i < 12; i++)
         for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
-    float v[8];
-    for (int i = 0; i < 8; i++) v[i] = threadIdx.x * 0.001f + i;
     for (int it = 0; it < iters; it++) {
 #pragma unroll
         for (int i = 0; i < 12; i++) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
-        if (NV > 0) probe_valu<NV>(v);
     }
     float s = 0.f;
     for (int i = 0; i < 12; i++) s += acc[i][0] + acc[i][7];
-    for (int i = 0; i < 8; i++) s += v[i];
     sink[blockIdx.x * 256 + threadIdx.x] = s;
-}
-
-// The stream of mfma16_kernel<60> cut into finer phases: NM 16x16x32 MFMAs, then 60 * NM / 24 FMAs, 24 / NM times
-// per round.
-template <int NM>
-__global__ __launch_bounds__(256) void mfma16_phases_kernel(float* sink, int iters) {
-    bf16x8 a, b;
-    probe_operands(a, b);
-    f32x4 acc[24];
-    for (int i = 0; i < 24; i++) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float v[8];
-    for (int i = 0; i < 8; i++) v[i] = threadIdx.x * 0.001f + i;
-    for (int it = 0; it < iters; it++) {
-#pragma unroll
-        for (int ph = 0; ph < 24 / NM; ph++) {
-#pragma unroll
-            for (int i = 0; i < NM; i++)
-                acc[ph * NM + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[ph * NM + i], 0, 0, 0);
-            probe_valu<60 * NM / 24>(v);
-        }
-    }
-    float s = 0.f;
-    for (int i = 0; i < 24; i++) s += acc[i][0] + acc[i][3];
-    for (int i = 0; i < 8; i++) s += v[i];
-    sink[blockIdx.x * 256 + threadIdx.x] = s;
-}
-
-// Slots of 32768 flop of MFMA (one 32x32x16 or two 16x16x32), every EVERY-th slot followed by the vector work of
-// one pair of softmax probabilities (two multiply-subtracts, two exponentials, one bf16 pack), every instruction
-// pinned in place by inline assembly.  A score costs 4 E flop (E = head dimension), so one pair per slot is the
-// softmax work per flop of E = 64 and one pair per two slots that of E = 128.  EVERY = 0 leaves the MFMAs alone.
-template <int SHAPE, int EVERY>
-__global__ __launch_bounds__(256) void mfma_slot_kernel(float* sink, int iters) {
-    bf16x8 a, b;
-    probe_operands(a, b);
-    f32x16 acc32[6];
-    f32x4 acc16[12];
-    for (int i = 0; i < 6; i++)
-        for (int r = 0; r < 16; r++) acc32[i][r] = 0.f;
-    for (int i = 0; i < 12; i++) acc16[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float v[8];
-    for (int i = 0; i < 8; i++) v[i] = threadIdx.x * 0.001f + i;
-    const float scale = 0.25f, ref = 3.f;
-    for (int it = 0; it < iters; it++) {
-#pragma unroll
-        for (int s = 0; s < 24; s++) {
-            if (SHAPE == 32) {
-                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc32[s % 6]) : "v"(a), "v"(b));
-            } else {
-                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc16[(2 * s) % 12]) : "v"(a), "v"(b));
-                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc16[(2 * s + 1) % 12]) : "v"(a), "v"(b));
-            }
-            if (EVERY > 0 && s % (EVERY > 0 ? EVERY : 1) == 0) {
-                float x0, x1;
-                uint32_t pk;
-                asm volatile("v_fma_f32 %0, %2, %4, -%5\n\tv_fma_f32 %1, %3, %4, -%5"
-                             : "=&v"(x0), "=&v"(x1)
-                             : "v"(v[s & 7]), "v"(v[(s + 3) & 7]), "s"(scale), "v"(ref));
-                asm volatile("s_nop 0\n\tv_exp_f32 %0, %0\n\tv_exp_f32 %1, %1" : "+v"(x0), "+v"(x1));
-                asm volatile("s_nop 0\n\tv_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(x0), "v"(x1));
-                v[s & 7] = __uint_as_float(pk & 0x3fffffffu);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    float sum = 0.f;
-    for (int i = 0; i < 6; i++) sum += acc32[i][0] + acc32[i][7];
-    for (int i = 0; i < 12; i++) sum += acc16[i][0] + acc16[i][3];
-    for (int i = 0; i < 8; i++) sum += v[i];
-    sink[blockIdx.x * 256 + threadIdx.x] = sum;
-}
-
-// The tile-loading pattern of the GEMM kernels with no arithmetic: 4 waves, each of which requests ten wave-wide
-// 16-byte asynchronous transfers to LDS per step (40 KB per workgroup and step: 320 pieces of 128 bytes, one per row,
-// rows of 6144 bytes picked by a hash of the workgroup and slot from the first `rows` rows of src), double buffered
-// exactly like the kernels: wait for the step in flight, barrier, request the next one, read a word of the current one.
-__global__ __launch_bounds__(256) void lds_fill_kernel(const uint8_t* __restrict__ src, uint32_t rows, int steps, float* sink) {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t fill_smem[];
-    constexpr int kLoads = 10, kStage = kLoads * 4096;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    uint32_t off[kLoads];
-    for (int i = 0; i < kLoads; i++) {
-        uint32_t row = ((blockIdx.x * 977u + (i * 4 + w) * 8 + (lane >> 3)) * 2654435761u >> 8) % rows;
-        off[i] = row * 6144u + (lane & 7) * 16;
-    }
-    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(uintptr_t)fill_smem + w * 1024));
-    const uint64_t base = reinterpret_cast<uint64_t>(src);
-    auto request = [&](int piece, int stage) {
-        const uint64_t b = base + (uint64_t)piece * 128;
-        const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
-                            (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-        for (int i = 0; i < kLoads; i++)
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(lds0 + stage * kStage + i * 4096), "v"(off[i]), "s"(ub)
-                         : "memory");
-    };
-    float acc = 0.f;
-    request(0, 0);
-    for (int kt = 0; kt < steps; kt++) {
-        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-        __builtin_amdgcn_s_barrier();
-        request((kt + 1) % 48, (kt + 1) & 1);
-        acc += *reinterpret_cast<const float*>(fill_smem + (kt & 1) * kStage + tid * 16);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-    sink[blockIdx.x * 256 + tid] = acc;
 }
 
 __global__ __launch_bounds__(256) void read_kernel(const float4* __restrict__ x, size_t n4, float* sink) {
@@ -224,92 +99,15 @@ extern "C" double chipmunk_probe_mfma_flops(int blocks_per_cu, int iters) {
     return kFlopsPerRound * 4.0 * (double)compute_units() * blocks_per_cu * iters;
 }
 
-extern "C" int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int valu_ops, int iters, float* sink,
-                                            void* stream) {
+extern "C" int32_t chipmunk_probe_mfma_bf16(int shape, int blocks_per_cu, int iters, float* sink, void* stream) {
     if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2)) return -1;
-    if ((shape != 16 && shape != 32) || (valu_ops != 0 && valu_ops != 64 && valu_ops != 128)) return -1;
+    if (shape != 16 && shape != 32) return -1;
     const int cus = compute_units();
     if (cus < 1) return -6;
     dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
     hipStream_t s = (hipStream_t)stream;
-    if (shape == 16) {
-        if (valu_ops == 0) hipLaunchKernelGGL(mfma16_kernel<0>, grid, block, 0, s, sink, iters);
-        else if (valu_ops == 64) hipLaunchKernelGGL(mfma16_kernel<64>, grid, block, 0, s, sink, iters);
-        else hipLaunchKernelGGL(mfma16_kernel<128>, grid, block, 0, s, sink, iters);
-    } else {
-        if (valu_ops == 0) hipLaunchKernelGGL(mfma32_kernel<0>, grid, block, 0, s, sink, iters);
-        else if (valu_ops == 64) hipLaunchKernelGGL(mfma32_kernel<64>, grid, block, 0, s, sink, iters);
-        else hipLaunchKernelGGL(mfma32_kernel<128>, grid, block, 0, s, sink, iters);
-    }
-    return status();
-}
-
-extern "C" int32_t chipmunk_probe_mfma_phases(int mfmas_per_phase, int blocks_per_cu, int iters, float* sink, void* stream) {
-    if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2)) return -1;
-    if (mfmas_per_phase != 24 && mfmas_per_phase != 12 && mfmas_per_phase != 8 && mfmas_per_phase != 4 &&
-        mfmas_per_phase != 2)
-        return -1;
-    const int cus = compute_units();
-    if (cus < 1) return -6;
-    dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
-    hipStream_t s = (hipStream_t)stream;
-    switch (mfmas_per_phase) {
-        case 24: hipLaunchKernelGGL(mfma16_phases_kernel<24>, grid, block, 0, s, sink, iters); break;
-        case 12: hipLaunchKernelGGL(mfma16_phases_kernel<12>, grid, block, 0, s, sink, iters); break;
-        case 8: hipLaunchKernelGGL(mfma16_phases_kernel<8>, grid, block, 0, s, sink, iters); break;
-        case 4: hipLaunchKernelGGL(mfma16_phases_kernel<4>, grid, block, 0, s, sink, iters); break;
-        case 2: hipLaunchKernelGGL(mfma16_phases_kernel<2>, grid, block, 0, s, sink, iters); break;
-        default: return -1;
-    }
-    return status();
-}
-
-extern "C" double chipmunk_probe_mfma_slots_flops(int blocks_per_cu, int iters) {
-    if ((blocks_per_cu != 1 && blocks_per_cu != 2) || iters < 1) return 0.0;
-    return 24.0 * 32 * 32 * 16 * 2 * 4.0 * (double)compute_units() * blocks_per_cu * iters;
-}
-
-extern "C" int32_t chipmunk_probe_mfma_slots(int shape, int blocks_per_cu, int head_dim, int iters, float* sink,
-                                             void* stream) {
-    if (!sink || iters < 1 || (blocks_per_cu != 1 && blocks_per_cu != 2) || (shape != 16 && shape != 32)) return -1;
-    if (head_dim != 0 && head_dim != 64 && head_dim != 128) return -1;
-    const int cus = compute_units();
-    if (cus < 1) return -6;
-    dim3 grid((unsigned)(cus * blocks_per_cu)), block(256);
-    hipStream_t s = (hipStream_t)stream;
-    const int every = head_dim == 0 ? 0 : head_dim / 64;
-    if (shape == 32) {
-        if (every == 0) hipLaunchKernelGGL((mfma_slot_kernel<32, 0>), grid, block, 0, s, sink, iters);
-        else if (every == 1) hipLaunchKernelGGL((mfma_slot_kernel<32, 1>), grid, block, 0, s, sink, iters);
-        else hipLaunchKernelGGL((mfma_slot_kernel<32, 2>), grid, block, 0, s, sink, iters);
-    } else {
-        if (every == 0) hipLaunchKernelGGL((mfma_slot_kernel<16, 0>), grid, block, 0, s, sink, iters);
-        else if (every == 1) hipLaunchKernelGGL((mfma_slot_kernel<16, 1>), grid, block, 0, s, sink, iters);
-        else hipLaunchKernelGGL((mfma_slot_kernel<16, 2>), grid, block, 0, s, sink, iters);
-    }
-    return status();
-}
-
-extern "C" double chipmunk_probe_lds_fill_bytes(int steps) {
-    if (steps < 1) return 0.0;
-    return 40960.0 * steps * 8.0 * (double)compute_units();
-}
-
-extern "C" int32_t chipmunk_probe_lds_fill(const void* src, size_t src_bytes, uint32_t rows, int steps, float* sink,
-                                           void* stream) {
-    if (!src || !sink || steps < 1 || rows < 1 || rows > (1u << 20)) return -1;
-    if (src_bytes < (size_t)rows * 6144 || (reinterpret_cast<uintptr_t>(src) & 15)) return -1;
-    const int cus = compute_units();
-    if (cus < 1) return -6;
-    constexpr int lds = 2 * 10 * 4096;   // two workgroups per compute unit, as in the GEMM kernels
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)lds_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-            return -6;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(lds_fill_kernel, dim3((unsigned)(cus * 8)), dim3(256), lds, (hipStream_t)stream,
-                       (const uint8_t*)src, rows, steps, sink);
+    if (shape == 16) hipLaunchKernelGGL(mfma16_kernel, grid, block, 0, s, sink, iters);
+    else hipLaunchKernelGGL(mfma32_kernel, grid, block, 0, s, sink, iters);
     return status();
 }
 

@@ -104,11 +104,13 @@ def mlp_weights(D, F, seed, device="cpu"):
     return w1, b1, w2, b2
 
 
-def mlp_steps(B, N, D, seed, device="cpu"):
-    """x1, x2: bf16 [B,N,D] for two consecutive diffusion steps."""
+def mlp_steps(B, N, D, seed, device="cpu", independent=False):
+    """x1, x2: bf16 [B,N,D] for two consecutive diffusion steps.  With `independent` the second step is a fresh
+    N(0,1) draw instead of a small perturbation of the first: the change of the activations is then as large as
+    the activations themselves (what parity tests of the delta kernels need in order to see the delta)."""
     g = generator(seed + 2000003, device)
     x1 = randn_bf16((B, N, D), g)
-    x2 = perturb_all(x1, g)
+    x2 = randn_bf16((B, N, D), g) if independent else perturb_all(x1, g)
     return x1, x2
 
 
@@ -157,11 +159,12 @@ def np_bf16_round(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).float().numpy()
 
 
-def stack_inputs(cfg, n_blocks, n_steps, seed, device="cpu"):
+def stack_inputs(cfg, n_blocks, n_steps, seed, device="cpu", x_sigma=COLD_SIGMA):
     """Inputs of a stack of DiT blocks over consecutive diffusion steps.
 
     Returns blocks[b] = dict(q, k, v, x: lists over steps of bf16 tensors; w1, b1, w2, b2).  Every block has its
-    own draws; step t+1 is step t perturbed by the recipe above with the block's fixed set of hot key tokens.
+    own draws; step t+1 is step t perturbed by the recipe above with the block's fixed set of hot key tokens
+    (x_sigma: the perturbation of the MLP input; parity tests raise it so that the MLP delta is not small).
     The blocks' inputs are independent of each other's outputs: projections and modulation between blocks are
     dense operations outside the method and are not modelled.
     """
@@ -179,7 +182,7 @@ def stack_inputs(cfg, n_blocks, n_steps, seed, device="cpu"):
             k.append(perturb_rows(k[-1], hot, g))
             v.append(perturb_rows(v[-1], hot, g))
             q.append(perturb_all(q[-1], g))
-            x.append(perturb_all(x[-1], g))
+            x.append(perturb_all(x[-1], g, x_sigma))
         w1, b1, w2, b2 = mlp_weights(D, F, seed + 7919 * (b + 1), device)
         blocks.append(dict(q=q, k=k, v=v, x=x, w1=w1, b1=b1, w2=w2, b2=b2))
     return blocks

@@ -1,6 +1,7 @@
 """The layer stack (several DiT blocks over consecutive diffusion steps) at a small shape: two blocks over three diffusion steps (one dense, two
 column-sparse), with and without the side-stream overlap of the MLP index work, against the oracle chained the
-same way.  The oracle takes its index lists from the GPU run (top-k parity has its own bit-exact tests on a shared
+same way.  The blocks' MLP inputs move by N(0,1) per step (x_sigma = 1), so the MLP delta is of the size of the cached
+output and a wrong delta cannot pass.  The oracle takes its index lists from the GPU run (top-k parity has its own bit-exact tests on a shared
 score buffer; here a borderline column chosen differently from slightly different scores would change what is
 compared), everything else it computes itself in fp64 from the same bf16 inputs."""
 import math
@@ -10,7 +11,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from parity import REL_TOL, rel_err
+from parity import REL_TOL, SCORE_TOL, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +44,7 @@ def test_stack_matches_chained_oracle(oracle, overlap):
     c, E = cfg["c"], cfg["E"]
     N = si.config_tokens(cfg)
     k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
-    inputs = si.stack_inputs(cfg, 2, 3, 5, DEV)
+    inputs = si.stack_inputs(cfg, 2, 3, 5, DEV, x_sigma=1.0)
     blocks, record = _run_gpu(cm, cfg, inputs, k_a, k_m, overlap)
     scale, act = 1.0 / math.sqrt(E), cm.ACT_GELU_TANH
     f32 = si.np_f32
@@ -52,21 +53,19 @@ def test_stack_matches_chained_oracle(oracle, overlap):
         # dense step
         q, k, v, x = (f32(inp[n][0]) for n in "qkvx")
         w1, b1, w2, b2 = (f32(inp[n]) for n in ("w1", "b1", "w2", "b2"))
-        # the cache O_dense - delta is a difference of two nearly equal tensors: each kernel call is held to the
-        # tolerance on what it computes (the dense output; the delta taken from the call's own bf16 base)
+        # every merge is compared with the oracle applied to the call's own bf16 base, under the one metric of
+        # tests/parity.py (floor: the larger of the output's and the update's RMS)
         dense_gpu = f32(blk.dense_out_copy).astype(np.float64)
         assert rel_err(dense_gpu, oracle.attn_dense(q, k, v, c, scale)) <= REL_TOL, (overlap, b)
         o_cache = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, dense_gpu, c, scale, -1.0)
         cache_gpu = f32(blk.o_cache).astype(np.float64)
-        assert rel_err(cache_gpu - dense_gpu, o_cache - dense_gpu) <= REL_TOL, (overlap, b)
+        assert rel_err(cache_gpu, o_cache, o_cache - dense_gpu) <= REL_TOL, (overlap, b)
         m_cache, a_cache, T_m = oracle.mlp_dense(x, w1, b1, w2, b2, c, act, a_ld=blk.a_cache.shape[-1])
         for step in (1, 2):
             g_attn, g_mlp, g_idx, g_cnt = record[(step, b)]
             q, k, v, x = (f32(inp[n][step]) for n in "qkvx")
-            # out = cache + delta where the two nearly cancel: the delta is what the kernel computes and what
-            # the tolerance applies to, so the oracle adds its delta to the call's own bf16 cache
             ref = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, cache_gpu, c, scale, 1.0)
-            assert rel_err(f32(g_attn) - cache_gpu, ref - cache_gpu) <= REL_TOL, (overlap, b, step)
+            assert rel_err(f32(g_attn), ref, ref - cache_gpu) <= REL_TOL, (overlap, b, step)
             # the GPU's index choice must be the exact top-k of the GPU's own scores
             T_gpu = torch.empty_like(blk.T)
             cm.mlp_tile_mean_preact(inp["x"][step], inp["w1"], T_gpu, c, blk.ws_tm)
@@ -74,9 +73,10 @@ def test_stack_matches_chained_oracle(oracle, overlap):
                                                 blk.T_m.view(-1, cfg["F"]).cpu().numpy(), k_m)
             assert np.array_equal(g_idx.view(-1, k_m).cpu().numpy(), ref_idx), (overlap, b, step)
             assert np.array_equal(g_cnt.view(-1).cpu().numpy(), ref_cnt)
-            assert rel_err(T_gpu.cpu().numpy(), oracle.mlp_tile_scores(x, w1, c)) <= 1e-3
+            assert rel_err(T_gpu.cpu().numpy(), oracle.mlp_tile_scores(x, w1, c)) <= SCORE_TOL
+            m_before = m_cache.copy()
             oracle.mlp_sparse_delta(x, w1, b1, w2, g_idx.cpu().numpy(), g_cnt.cpu().numpy(), a_cache, m_cache, c, act)
-            assert rel_err(f32(g_mlp), m_cache) <= REL_TOL, (overlap, b, step)
+            assert rel_err(f32(g_mlp), m_cache, m_cache - m_before) <= REL_TOL, (overlap, b, step)
         assert rel_err(f32(blk.a_cache), a_cache) <= REL_TOL
 
 
@@ -87,7 +87,7 @@ def test_stack_overlap_equals_serial():
     cfg = si.CONFIGS["tiny"]
     N = si.config_tokens(cfg)
     k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
-    inputs = si.stack_inputs(cfg, 3, 3, 9, DEV)
+    inputs = si.stack_inputs(cfg, 3, 3, 9, DEV, x_sigma=1.0)
     _, serial = _run_gpu(cm, cfg, inputs, k_a, k_m, False)
     _, overlapped = _run_gpu(cm, cfg, inputs, k_a, k_m, True)
     for key in serial:
@@ -104,7 +104,7 @@ def test_stack_sparse_step_as_hip_graph():
     cfg = si.CONFIGS["tiny"]
     N = si.config_tokens(cfg)
     k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
-    inputs = si.stack_inputs(cfg, 2, 3, 11, DEV)
+    inputs = si.stack_inputs(cfg, 2, 3, 11, DEV, x_sigma=1.0)
     blocks = [stack.Block(inp, cfg["c"], k_a, k_m) for inp in inputs]
     stack.dense_step(blocks, 0)
     torch.cuda.synchronize()
@@ -149,7 +149,7 @@ def test_stack_dense_refresh_with_stale_normalisers(oracle):
     c, E = cfg["c"], cfg["E"]
     N = si.config_tokens(cfg)
     k_a, k_m = si.kept(N, cfg["attn_keep"]), si.kept(cfg["F"], cfg["mlp_keep"])
-    inputs = si.stack_inputs(cfg, 2, 4, 13, DEV)
+    inputs = si.stack_inputs(cfg, 2, 4, 13, DEV, x_sigma=1.0)
     blocks = [stack.Block(inp, c, k_a, k_m) for inp in inputs]
     scale = 1.0 / math.sqrt(E)
     f32 = si.np_f32
@@ -181,9 +181,9 @@ def test_stack_dense_refresh_with_stale_normalisers(oracle):
         assert np.abs(lse - (m_ref + np.log(l_ref))).max() <= 2e-3
         cache_gpu = f32(blk.o_cache).astype(np.float64)
         o_cache = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, dense_gpu, c, scale, -1.0)
-        assert rel_err(cache_gpu - dense_gpu, o_cache - dense_gpu) <= REL_TOL, b
+        assert rel_err(cache_gpu, o_cache, o_cache - dense_gpu) <= REL_TOL, b
         blk.attn_delta(3)
         torch.cuda.synchronize()
         q, k, v = (f32(inp[n][3]) for n in "qkv")
         ref = oracle.attn_sparse_delta(q, k, v, idx_a, cnt_a, cache_gpu, c, scale, 1.0)
-        assert rel_err(f32(blk.attn_out) - cache_gpu, ref - cache_gpu) <= REL_TOL, b
+        assert rel_err(f32(blk.attn_out), ref, ref - cache_gpu) <= REL_TOL, b

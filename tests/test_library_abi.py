@@ -49,6 +49,15 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 64, 8, 0.1, 1.0, None) == -4           # c
     assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, -0.1, 1.0, None) == -2         # scale
     assert f(P(0x1008), a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, 0.1, 1.0, None) == -3  # alignment
+    nan, inf = float("nan"), float("inf")
+    assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, nan, 1.0, None) == -2          # NaN scale: nothing launched
+    assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, inf, 1.0, None) == -2
+    assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, 0.0, 1.0, None) == -2
+    assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, 0.1, nan, None) == -2          # NaN o_scale
+    assert f(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, 0.1, -inf, None) == -2
+    # K/V rows are addressed with 32-bit byte offsets inside a head: N * E * 2 must stay below 2^32
+    assert f(a, a, a, a, a, a, a, 1, 1, 1 << 24, 128, 192, 8, 0.1, 1.0, None) == -2
+    assert f(a, a, a, a, a, a, a, 1, 1, 1 << 25, 64, 192, 8, 0.1, 1.0, None) == -2
     # top-k
     t = lib.chipmunk_topk_cols
     assert t(None, None, 1, 8, 8, 2, a, a, 2, None) == -1
@@ -75,16 +84,27 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     d = lib.chipmunk_attn_dense
     assert d(a, a, a, a, a, 128, 1, 1, 128, 128, 192, 0.1, None, 0, None) == -5        # colsum needs ws
     assert d(a, a, a, a, a, 100, 1, 1, 128, 128, 192, 0.1, a, 1 << 20, None) == -2     # ld_colsum < N
+    assert d(a, a, a, a, None, 0, 1, 1, 1 << 24, 128, 192, 0.1, None, 0, None) == -2   # N * E * 2 >= 2^32
     cs = lib.chipmunk_attn_colsum_stale
     assert cs(a, a, None, a, a, 128, 1, 1, 128, 128, 192, 0.1, None) == -1             # normalisers are required
     assert cs(a, a, a, a, a, 100, 1, 1, 128, 128, 192, 0.1, None) == -2                # ld_colsum < N
     assert cs(a, a, a, a, a, 128, 1, 1, 128, 96, 192, 0.1, None) == -4                 # E
     assert cs(a, a, P(0x1002), a, a, 128, 1, 1, 128, 128, 192, 0.1, None) == -3        # fp32 alignment
+    assert cs(a, a, a, a, a, 1 << 24, 1, 1, 1 << 24, 128, 192, 0.1, None) == -2        # N * E * 2 >= 2^32
+    assert cs(a, a, a, a, a, 128, 1, 1, 128, 128, 192, float("nan"), None) == -2
     fu = lib.chipmunk_attn_dense_colsum_stale
     assert fu(a, a, a, a, None, a, a, 128, None, None, 1, 1, 128, 128, 192, 0.1, None) == -1   # normalisers required
     assert fu(a, a, a, a, a, a, a, 128, a, None, 1, 1, 128, 128, 192, 0.1, None) == -1         # new_m without new_l
     assert fu(a, a, a, a, a, a, a, 100, None, None, 1, 1, 128, 128, 192, 0.1, None) == -2      # ld_colsum < N
     assert fu(a, a, a, a, a, a, a, 128, None, None, 1, 1, 128, 128, 160, 0.1, None) == -4      # c
+    assert fu(a, a, a, a, a, a, a, 1 << 24, None, None, 1, 1, 1 << 24, 128, 192, 0.1, None) == -2   # N * E * 2 >= 2^32
+    # the token-merged pre-activation: sizes the size query refuses are refused by the call as well
+    tm = lib.chipmunk_mlp_tile_mean_preact
+    assert lib.chipmunk_mlp_tile_mean_workspace_bytes(1, 1024, 256, 1024, 128) > 0
+    assert lib.chipmunk_mlp_tile_mean_workspace_bytes(1, 1024, 200, 1024, 128) == 0
+    assert lib.chipmunk_mlp_tile_mean_workspace_bytes(70000, 128, 128, 64, 128) > 0       # more chunks than one grid axis holds
+    assert tm(a, a, a, 1, 1024, 256, 1024, 128, None, 0, None) == -5
+    assert tm(a, a, a, 1, 1024, 256, 1024, 100, a, 1 << 30, None) == -4
 
 
 def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
@@ -93,21 +113,16 @@ def test_ceiling_probe_library_loads_and_rejects_bad_arguments():
     text = open(os.path.join(ROOT, "paper_2506_03275_amd", "probe", "ceilings.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = sorted(set(re.findall(r"\b(chipmunk_probe_[a-z0-9_]+)\s*\(", text)))
-    assert len(declared) == 9
+    assert declared == ["chipmunk_probe_copy", "chipmunk_probe_mfma_bf16", "chipmunk_probe_mfma_flops",
+                        "chipmunk_probe_read"]
     for name in declared:
         assert hasattr(lib, name)
     P = ctypes.c_void_p
     a = P(0x1000)
     assert lib.chipmunk_probe_mfma_flops(3, 10) == 0.0
-    assert lib.chipmunk_probe_mfma_bf16(16, 1, 0, 10, None, None) == -1
-    assert lib.chipmunk_probe_mfma_bf16(24, 1, 0, 10, a, None) == -1      # shape
-    assert lib.chipmunk_probe_mfma_bf16(32, 1, 32, 10, a, None) == -1     # valu_ops
-    assert lib.chipmunk_probe_mfma_slots(8, 1, 64, 10, a, None) == -1     # shape
-    assert lib.chipmunk_probe_mfma_slots(16, 1, 1, 10, a, None) == -1     # head dimension of the vector mix
-    assert lib.chipmunk_probe_mfma_phases(5, 1, 10, a, None) == -1         # phase length
-    assert lib.chipmunk_probe_mfma_slots_flops(1, 0) == 0.0
-    assert lib.chipmunk_probe_lds_fill(a, 6144, 2, 10, a, None) == -1     # src smaller than rows * 6144
-    assert lib.chipmunk_probe_lds_fill_bytes(0) == 0.0
+    assert lib.chipmunk_probe_mfma_bf16(16, 1, 10, None, None) == -1
+    assert lib.chipmunk_probe_mfma_bf16(24, 1, 10, a, None) == -1         # shape
+    assert lib.chipmunk_probe_mfma_bf16(32, 3, 10, a, None) == -1         # workgroups per compute unit
     assert lib.chipmunk_probe_read(a, 24, a, None) == -1                  # bytes % 16
     assert lib.chipmunk_probe_copy(a, P(0x2008), 64, None) == -1          # alignment
 
