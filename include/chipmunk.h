@@ -172,6 +172,21 @@ int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16_t* w1, flo
                                       int B, int N, int D, int F, int c,
                                       void* ws, size_t ws_bytes, void* stream);
 
+/* chipmunk_mlp_tile_mean_preact for callers that cannot allocate device memory and so have no workspace to hand
+ * in: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and the same result up to the summation order of the contraction's pieces; the workspace is a fixed
+ * array of chipmunk_mlp_tile_mean_preact_static_capacity() bytes (32 MiB) in device memory that the library holds
+ * on every GPU it runs on until the process ends.  The call allocates and frees nothing.  Problems whose chunk
+ * means alone (B * NB * 2 * D bf16 values) exceed the array are rejected with CHIPMUNK_ERR_WORKSPACE and nothing is
+ * launched; below that limit the contraction is cut into fewer pieces where the general entry point's workspace
+ * would not fit.  All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different
+ * streams, or different host threads) race and must be ordered by the caller; nothing in the array has to be
+ * cleared between calls.  The first call on a device looks the array's address up (no allocation either); make
+ * that call outside stream capture. */
+size_t chipmunk_mlp_tile_mean_preact_static_capacity(void);
+int32_t chipmunk_mlp_tile_mean_preact_static(const uint16_t* x, const uint16_t* w1, float* T,
+                                             int B, int N, int D, int F, int c, void* stream);
+
 /* Workspace bytes of chipmunk_mlp_sparse_delta (0 on bad arguments). */
 size_t chipmunk_mlp_workspace_bytes(int B, int N, int D, int F, int c, int k_stride);
 

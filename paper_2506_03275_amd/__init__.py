@@ -38,6 +38,8 @@ _SIGNATURES = {
                                          ctypes.c_int32),
     "chipmunk_mlp_tile_mean_workspace_bytes": ([_c_int] * 5, _c_size),
     "chipmunk_mlp_tile_mean_preact": ([_c_ptr] * 3 + [_c_int] * 5 + [_c_ptr, _c_size, _c_ptr], ctypes.c_int32),
+    "chipmunk_mlp_tile_mean_preact_static_capacity": ([], _c_size),
+    "chipmunk_mlp_tile_mean_preact_static": ([_c_ptr] * 3 + [_c_int] * 5 + [_c_ptr], ctypes.c_int32),
     "chipmunk_mlp_workspace_bytes": ([_c_int] * 6, _c_size),
     "chipmunk_mlp_sparse_delta": ([_c_ptr] * 7 + [_c_i64, _c_ptr] + [_c_int] * 7 + [_c_ptr, _c_size, _c_ptr],
                                   ctypes.c_int32),
@@ -206,6 +208,16 @@ def mlp_tile_mean_preact(x, w1, T, c, ws):
                                                 B, N, D, F, c, _ptr(ws, torch.uint8, "ws"),
                                                 0 if ws is None else ws.numel(), _stream()),
            "chipmunk_mlp_tile_mean_preact")
+
+
+def mlp_tile_mean_preact_static(x, w1, T, c):
+    """mlp_tile_mean_preact on the library's own fixed scratch array: no workspace argument, no allocation."""
+    B, N, D = x.shape
+    F = w1.shape[0]
+    bf = torch.bfloat16
+    _check(load().chipmunk_mlp_tile_mean_preact_static(_ptr(x, bf, "x"), _ptr(w1, bf, "w1"),
+                                                       _ptr(T, torch.float32, "T"), B, N, D, F, c, _stream()),
+           "chipmunk_mlp_tile_mean_preact_static")
 
 
 def mlp_workspace_bytes(B, N, D, F, c, k_stride):

@@ -20,6 +20,8 @@
 // writes a_cache only and GEMM2 reads its A operand from a_cache and adds b2.
 #include "common.h"
 
+#include <mutex>
+
 namespace chipmunk {
 
 constexpr int kBN = 128;  // neurons (GEMM1) or output columns (GEMM2) per workgroup
@@ -747,5 +749,58 @@ extern "C" int32_t chipmunk_mlp_tile_mean_preact(const uint16_t* x, const uint16
     const int pieces = tile_mean_pieces((int)units, F);
     size_t need = tile_mean_bytes(B, N, D, F, c, pieces);
     if (!ws || need == 0 || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
+    return run_tile_mean(x, w1, T, B, N, D, F, c, ws, pieces, (hipStream_t)stream);
+}
+
+// ---- the token-merged pre-activation for callers that cannot allocate ---------------------------------------
+// Same kernels as chipmunk_mlp_tile_mean_preact; the workspace is a fixed array in device memory that belongs to
+// the library.  Each GPU the library runs on holds its own copy at its own address: the address is looked up once
+// per device (with that device current) and kept; host code passes that address, never the array's name, to the
+// kernels.
+namespace chipmunk {
+
+constexpr size_t kStaticScratchBytes = 32u << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+static std::mutex scratch_mutex;
+static void* scratch_address[kMaxDevices];   // per device, 0 until looked up
+
+static int32_t scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CHIPMUNK_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_address[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CHIPMUNK_ERR_LAUNCH;
+        scratch_address[dev] = ptr;
+    }
+    *out = scratch_address[dev];
+    return CHIPMUNK_OK;
+}
+
+}  // namespace chipmunk
+
+extern "C" size_t chipmunk_mlp_tile_mean_preact_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" int32_t chipmunk_mlp_tile_mean_preact_static(const uint16_t* x, const uint16_t* w1, float* T, int B, int N,
+                                                        int D, int F, int c, void* stream) {
+    if (!x || !w1 || !T) return CHIPMUNK_ERR_NULL;
+    int32_t st = check_mlp_shapes(B, N, D, F, c);
+    if (st != CHIPMUNK_OK) return st;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(T)) return CHIPMUNK_ERR_ALIGN;
+    const int64_t units = (int64_t)B * ((N + c - 1) / c);
+    if (units > 0x7fffff || units * 2 * D * 2 >= (1LL << 32)) return CHIPMUNK_ERR_SHAPE;
+    // as many pieces of the contraction as the general entry point would use, halved until the chunk means and the
+    // pieces' partial results fit the array; with one piece the scores go straight to T
+    int pieces = tile_mean_pieces((int)units, F);
+    while (pieces > 1 && tile_mean_bytes(B, N, D, F, c, pieces) > kStaticScratchBytes) pieces /= 2;
+    const size_t need = tile_mean_bytes(B, N, D, F, c, pieces);
+    if (need == 0 || need > kStaticScratchBytes) return CHIPMUNK_ERR_WORKSPACE;   // the chunk means alone do not fit
+    void* ws = nullptr;
+    st = scratch_of_current_device(&ws);
+    if (st != CHIPMUNK_OK) return st;
+    // every byte of the array that the kernels read in this call is written by this call first (the chunk means
+    // by chunk_mean_kernel, every piece's partial scores by the scores GEMM): nothing has to start at zero
     return run_tile_mean(x, w1, T, B, N, D, F, c, ws, pieces, (hipStream_t)stream);
 }
