@@ -20,6 +20,8 @@
 // Each wave owns NQB blocks of 16 queries (c = 64*NQB).
 #include "common.h"
 
+#include <type_traits>
+
 namespace chipmunk {
 
 struct AttnParams {
@@ -74,34 +76,60 @@ struct AttnState {
 // next to the exponentials of tile t (VALU), and the max bookkeeping of tile t+1
 // (VALU) next to the P.V products of tile t (MFMA).
 
+// LDS reads take byte addresses in registers (the LDS base is already added) plus compile-time offsets, so that the
+// offsets become the immediate field of the read instead of an address computation per read.
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>((uintptr_t)addr);
+}
+__device__ __forceinline__ short4v lds_read_tr16_at(uint32_t addr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<__attribute__((address_space(3))) short4v*>((uintptr_t)addr));
+}
+
 // S^T = K Q^T - m for one tile: raw scores relative to the reference max (the MFMA adds -m for free where a
-// separate subtraction would cost one vector instruction per score); rows at or beyond `count` are set to -inf
-// when MASK.
-template <int E, int NQB, bool MASK>
-__device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<E, NQB>& st, const uint8_t* sK,
-                                            int koff, int kv0, int count, int g) {
+// separate subtraction would cost one vector instruction per score).  kaddr[es]: the lane's read address for
+// contraction slice es in tile buffer 0; tile_off: byte offset of the tile buffer (compile-time at the call).
+// between(j), j = 0 .. E/16 - 1, is called after the j-th group of NQB products: the kernel issues one of the next
+// step's tile transfers there, so that the transfers are spread over the products instead of queueing up in one
+// burst during which the wave issues nothing else.
+constexpr int kKPrefetch = 3;  // K operands requested ahead of the products that consume them
+
+template <int E, int NQB, typename Between>
+__device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<E, NQB>& st, const uint32_t (&kaddr)[E / 32],
+                                            int tile_off, Between&& between) {
     constexpr int ROWB = E * 2;
+    constexpr int NG = E / 16;   // groups of NQB products: group j = contraction slice j / 2, key rows 16 (j % 2) ..
+    bf16x8 kop[NG];
 #pragma unroll
-    for (int es = 0; es < E / 32; es++) {
+    for (int j = 0; j < kKPrefetch; j++) kop[j] = lds_read_b128(kaddr[j / 2] + tile_off + (j % 2) * 16 * ROWB);
+    __builtin_amdgcn_sched_group_barrier(0x100, kKPrefetch, 0);  // the LDS reads lead the block
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
-            bf16x8 kop = *reinterpret_cast<const bf16x8*>(sK + u * 16 * ROWB + (koff ^ (64 * es)));
+    for (int j = 0; j < NG; j++) {
+        const int es = j / 2, u = j % 2;
+        if (j + kKPrefetch < NG) {
+            const int jn = j + kKPrefetch;
+            kop[jn] = lds_read_b128(kaddr[jn / 2] + tile_off + (jn % 2) * 16 * ROWB);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int qb = 0; qb < NQB; qb++)
+            S[u][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[j], st.Q[es][qb], es == 0 ? st.negm[qb] : S[u][qb], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NQB, 0);
+        between(j);
+    }
+}
+
+// The last tile of a unit: rows at or beyond `count` score -inf.
+template <int NQB>
+__device__ __forceinline__ void attn_mask_tail(f32x4 (&S)[2][NQB], int kv0, int count, int g) {
+#pragma unroll
+    for (int u = 0; u < 2; u++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            bool dead = kv0 + u * 16 + 4 * g + r >= count;
 #pragma unroll
             for (int qb = 0; qb < NQB; qb++)
-                S[u][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, st.Q[es][qb], es == 0 ? st.negm[qb] : S[u][qb], 0, 0, 0);
+                if (dead) S[u][qb][r] = -INFINITY;
         }
-    }
-    if (MASK) {
-#pragma unroll
-        for (int u = 0; u < 2; u++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                bool dead = kv0 + u * 16 + 4 * g + r >= count;
-#pragma unroll
-                for (int qb = 0; qb < NQB; qb++)
-                    if (dead) S[u][qb][r] = -INFINITY;
-            }
-    }
 }
 
 // Raise the reference max where this tile's relative scores exceed the slack
@@ -174,7 +202,7 @@ __device__ __forceinline__ void row16_sums_to_lds(const float (&acc)[8], float* 
 // reference st.m and wq = exp2(st.m * sl2 + off) per query, off = -prev_m2 - log2(prev_l) (-inf: no such query).
 template <int E, int NQB, bool COLSUM = false>
 __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB],
-                                                    const uint8_t* sV, int voff, float sl2, bf16x8 ones,
+                                                    const uint32_t (&vaddr)[E / 16], int tile_off, float sl2, bf16x8 ones,
                                                     const float* off = nullptr, float* part = nullptr, int g = 0,
                                                     int l16 = 0) {
     constexpr int ROWB = E * 2;
@@ -183,8 +211,8 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
     short4v vlo[NEB], vhi[NEB];
 #pragma unroll
     for (int eb = 0; eb < kVPrefetch; eb++) {
-        vlo[eb] = lds_read_tr16(sV + (voff ^ (32 * eb)));
-        vhi[eb] = lds_read_tr16(sV + 16 * ROWB + (voff ^ (32 * eb)));
+        vlo[eb] = lds_read_tr16_at(vaddr[eb] + tile_off);
+        vhi[eb] = lds_read_tr16_at(vaddr[eb] + tile_off + 16 * ROWB);
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * kVPrefetch, 0);  // the LDS reads lead the block
     bf16x8 pop[NQB];
@@ -217,8 +245,8 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
 #pragma unroll
     for (int eb = 0; eb < NEB; eb++) {
         if (eb + kVPrefetch < NEB) {
-            vlo[eb + kVPrefetch] = lds_read_tr16(sV + (voff ^ (32 * (eb + kVPrefetch))));
-            vhi[eb + kVPrefetch] = lds_read_tr16(sV + 16 * ROWB + (voff ^ (32 * (eb + kVPrefetch))));
+            vlo[eb + kVPrefetch] = lds_read_tr16_at(vaddr[eb + kVPrefetch] + tile_off);
+            vhi[eb + kVPrefetch] = lds_read_tr16_at(vaddr[eb + kVPrefetch] + tile_off + 16 * ROWB);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
         short8v both = __builtin_shufflevector(vlo[eb], vhi[eb], 0, 1, 2, 3, 4, 5, 6, 7);
@@ -295,7 +323,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             st.Q[es][qb] = __builtin_bit_cast(bf16x8, val);
         }
     }
-    const bool wave_active = w * NQB * 16 < rows_valid;
+    const bool wave_active = wu * NQB * 16 < rows_valid;   // wave-uniform, and known to be
     const float slack = kRescaleSlack / p.sl2;
     // FUSED: -prev_m (log2 units) - log2(prev_l) of the lane's queries; -inf drops a query row that does not exist
     float off[NQB];
@@ -324,10 +352,23 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 
-    // per-lane LDS read offsets (bytes) inside a 16-row group of a tile
+    // per-lane LDS read addresses (bytes, the LDS base included) inside a 16-row group of tile buffer 0: one per
+    // contraction slice, because the slice number enters through the XOR swizzle, not additively
     const int koff = l16 * ROWB + ((g ^ swizzle<E>(l16)) * 16);
     const int vrow = 4 * g + (l16 >> 2);
     const int voff = vrow * ROWB + (((((l16 & 3) >> 1)) ^ swizzle<E>(vrow)) * 16) + 8 * (l16 & 1);
+    const uint32_t smem_at = (uint32_t)(uintptr_t)CHIPMUNK_LDS_PTR(smem);
+    uint32_t kaddr[E / 32], vaddr[E / 16];
+#pragma unroll
+    for (int es = 0; es < E / 32; es++) kaddr[es] = smem_at + (uint32_t)(koff ^ (64 * es));
+#pragma unroll
+    for (int eb = 0; eb < E / 16; eb++) vaddr[eb] = smem_at + (uint32_t)(voff ^ (32 * eb));
+    // The LDS base is a link-time constant; left visible, the compiler would keep the offsets without it and add
+    // it again at every read.  Behind this barrier each address is just a register.
+#pragma unroll
+    for (int es = 0; es < E / 32; es++) asm volatile("" : "+v"(kaddr[es]));
+#pragma unroll
+    for (int eb = 0; eb < E / 16; eb++) asm volatile("" : "+v"(vaddr[eb]));
 
     // Gather bookkeeping.  Load i of this wave fills rows (i*NWAVES+w)*RPI .. +RPI-1 of
     // the tile; the lane owns row (i*NWAVES+w)*RPI + lane/CH, LDS chunk position lane%CH,
@@ -335,80 +376,103 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const int sel = lane / CH;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
     const int ntiles = (count + kTileRows - 1) / kTileRows;
+    uint32_t chunk_off[NI];  // byte offset of the lane's chunk inside the row it fetches
+#pragma unroll
+    for (int i = 0; i < NI; i++) chunk_off[i] = (uint32_t)(((lane % CH) ^ swizzle<E>((i * NWAVES + w) * RPI + sel)) * 16);
+
+    // K, V and the unit's index list are read through buffer resources: the hardware checks every
+    // offset against the tensor's size (an out-of-range access returns zero), so neither the column
+    // numbers nor the positions in the list are clamped with vector instructions.  A slot of the list
+    // at or beyond `count` reads as column 0: a valid row, whose scores the last tile masks.
+    const i32x4 kbuf = raw_buffer_words(kh, (uint32_t)p.N * ROWB);
+    const i32x4 vbuf = raw_buffer_words(vh, (uint32_t)p.N * ROWB);
+    const int32_t* idxg = p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
+    const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(idxg, idxg ? (uint32_t)count * 4u : 0u);
 
     // Every lane fetches the selected column of the tile row it fills, one step ahead of
     // the gather that uses it: the loads are issued behind that step's tile transfers and
     // have landed, like those, when the next step starts with its wait for all memory.
-    // colv[s][i] belongs to row (i*NWAVES+w)*RPI + sel of the s-th tile of a step.
-    const int32_t* idxg = p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
+    // colv[s][i] belongs to row (i*NWAVES+w)*RPI + sel of the s-th tile of a step; in the list
+    // that is position  step's first column + s*kTileRows + i*NWAVES*RPI + (w*RPI + sel): the
+    // last term is the lane's own (next_pos), the others are immediates of the loads.
     int colv[kTilesPerStep][NI];
-    auto load_cols = [&](int tile0) {  // columns of tiles tile0 .. tile0+kTilesPerStep-1
-        const int last = count - 1;
-#pragma unroll
-        for (int s = 0; s < kTilesPerStep; s++)
-#pragma unroll
-            for (int i = 0; i < NI; i++) colv[s][i] = min((tile0 + s) * kTileRows + (i * NWAVES + w) * RPI + sel, last);
+    int next_pos = w * RPI + sel;   // the lane's position in the list for (s = 0, i = 0) of the next step to load
+    int next_off = next_pos * 4;    // ... and its byte offset
+    auto load_cols = [&]() {
         if (idxg) {
 #pragma unroll
             for (int s = 0; s < kTilesPerStep; s++)
 #pragma unroll
-                for (int i = 0; i < NI; i++) colv[s][i] = idxg[colv[s][i]];
+                for (int i = 0; i < NI; i++)
+                    colv[s][i] = __builtin_amdgcn_raw_buffer_load_b32(ibuf, next_off + (s * kTileRows + i * NWAVES * RPI) * 4, 0, 0);
+        } else {  // dense: column = position
+#pragma unroll
+            for (int s = 0; s < kTilesPerStep; s++)
+#pragma unroll
+                for (int i = 0; i < NI; i++) colv[s][i] = min(next_pos + s * kTileRows + i * NWAVES * RPI, p.N - 1);
         }
+        next_pos += kTilesPerStep * kTileRows;
+        next_off += kTilesPerStep * kTileRows * 4;
     };
-    auto gather = [&](int half) {  // fills buffers half*kTilesPerStep .. with the tiles whose columns are in colv
-#pragma unroll
-        for (int s = 0; s < kTilesPerStep; s++)
-#pragma unroll
-            for (int i = 0; i < NI; i++) {
-                int row = (i * NWAVES + w) * RPI + sel;
-                // byte offset of this lane's chunk inside the head's K (and V) matrix
-                // clamped here, where the load has landed anyway, not where it is issued
-                uint32_t goff = (uint32_t)min(max(colv[s][i], 0), p.N - 1) * ROWB + (uint32_t)(((lane % CH) ^ swizzle<E>(row)) * 16);
-                uint32_t dst = lds0 + (uint32_t)((half * kTilesPerStep + s) * STAGE + i * NWAVES * 1024);
-                load_global_to_lds_16B(kh, goff, dst);
-                load_global_to_lds_16B(vh, goff, dst + TILE);
-            }
+    // One of the E/16 transfers that fill buffer half `half` with the tiles whose columns are in colv: piece j is
+    // the K (j even) or V (j odd) part of load i = (j/2) % NI of tile s = j / (2 NI).
+    auto gather_piece = [&](auto half_c, int j) {
+        constexpr int half = decltype(half_c)::value;
+        const int s = j / (2 * NI), i = (j / 2) % NI;
+        // byte offset of this lane's chunk inside the head's K (and V) matrix
+        const uint32_t goff = (uint32_t)colv[s][i] * ROWB + chunk_off[i];
+        const uint32_t dst = lds0 + (uint32_t)((half * kTilesPerStep + s) * STAGE + i * NWAVES * 1024);
+        if (j & 1) load_buffer_to_lds_16B(vbuf, goff, dst + TILE);
+        else load_buffer_to_lds_16B(kbuf, goff, dst);
     };
+    static_assert(kTilesPerStep * NI * 2 == E / 16, "one transfer per group of score products");
 
     // The query loads must not be left pending into the loop: a wait for them inside
     // the loop would also wait for every tile transfer in flight.  The columns of the
     // first step are requested beside them: one round trip for both.
-    load_cols(0);
+    load_cols();
     wait_all_memory();
 
     // first step in flight; columns of the second step requested
-    gather(0);
-    load_cols(kTilesPerStep);
+#pragma unroll
+    for (int j = 0; j < E / 16; j++) gather_piece(std::integral_constant<int, 0>{}, j);
+    load_cols();
 
-    int half = 0;  // which half of the buffers holds the step being consumed
-#pragma unroll 1
-    for (int t = 0; t < ntiles; t += kTilesPerStep) {
+    // One step: the kTilesPerStep tiles in buffer half `half`.  The half is a compile-time constant (the loop
+    // below alternates two copies of the step), so every LDS offset of the step is an immediate of its read.
+    // The next step's tiles are requested between the score products of this step's first tile, and the columns
+    // of the step after that behind them.  Both happen on every step: past the end of the list the columns read
+    // as 0 (the buffer's range check), so the last step fetches row 0 into buffers nobody reads.
+    auto step = [&](auto half_c, int t) {
+        constexpr int half = decltype(half_c)::value;
         wait_all_memory();
         __syncthreads();  // this step's tiles have landed for every wave; the other half is free to refill
-        if (t + kTilesPerStep < ntiles) {
-            gather(half ^ 1);
-            load_cols(t + 2 * kTilesPerStep);
-        }
         if (FUSED && t > 0) flush_column_sums(t - kTilesPerStep);
-        if (wave_active) {
 #pragma unroll
-            for (int s = 0; s < kTilesPerStep; s++) {
-                if (t + s < ntiles) {
-                    const uint8_t* cK = smem + (half * kTilesPerStep + s) * STAGE;
-                    f32x4 S[2][NQB];
-                    if (t + s + 1 < ntiles)
-                        attn_scores<E, NQB, false>(S, st, cK, koff, (t + s) * kTileRows, count, g);
-                    else
-                        attn_scores<E, NQB, true>(S, st, cK, koff, (t + s) * kTileRows, count, g);
-                    attn_update_max<E, NQB>(st, S, t + s == 0, p.sl2, slack);
-                    attn_weights_and_pv<E, NQB, FUSED>(
-                        st, S, cK + TILE, voff, p.sl2, ones, off,
-                        s_part + ((((t / kTilesPerStep) & 1) * NWAVES + w) * kTilesPerStep + s) * kTileRows, g, l16);
-                }
+        for (int s = 0; s < kTilesPerStep; s++) {
+            const int tile_off = (half * kTilesPerStep + s) * STAGE;   // a constant once the loop over s is unrolled
+            f32x4 S[2][NQB];
+            if (s == 0) {
+                attn_scores<E, NQB>(S, st, kaddr, tile_off,
+                                    [&](int j) { gather_piece(std::integral_constant<int, half ^ 1>{}, j); });
+                load_cols();
+            } else {
+                if (t + s >= ntiles) break;
+                attn_scores<E, NQB>(S, st, kaddr, tile_off, [](int) {});
             }
+            if (t + s + 1 >= ntiles) attn_mask_tail<NQB>(S, (t + s) * kTileRows, count, g);
+            attn_update_max<E, NQB>(st, S, t + s == 0, p.sl2, slack);
+            attn_weights_and_pv<E, NQB, FUSED>(st, S, vaddr, tile_off + TILE, p.sl2, ones, off,
+                                               s_part + ((half * NWAVES + w) * kTilesPerStep + s) * kTileRows, g, l16);
         }
-        half ^= 1;
+    };
+#pragma unroll 1
+    for (int t = 0; t < ntiles; t += 2 * kTilesPerStep) {
+        step(std::integral_constant<int, 0>{}, t);
+        if (t + kTilesPerStep >= ntiles) break;
+        step(std::integral_constant<int, 1>{}, t + kTilesPerStep);
     }
+    wait_all_memory();  // the last step's transfers into the unused half must have landed before the wave may end
     if (FUSED) {
         __syncthreads();  // the last step's partial sums are complete
         flush_column_sums(((ntiles - 1) / kTilesPerStep) * kTilesPerStep);

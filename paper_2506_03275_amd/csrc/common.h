@@ -54,6 +54,35 @@ __device__ __forceinline__ void load_global_to_lds_16B(const void* base, uint32_
                  : "memory");
 }
 
+// Raw buffer resource (no stride, no swizzle) over `bytes` bytes at `base`, both wave-uniform.  Loads through it
+// are range-checked by the hardware on (per-lane offset + immediate offset): an access that starts at or beyond
+// `bytes` returns zero instead of touching memory.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+__device__ __forceinline__ i32x4 raw_buffer_words(const void* base, uint32_t bytes) {
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(b >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// The same asynchronous 16-byte load to LDS through a buffer resource: the global address is the buffer's base +
+// the lane's byte_offset (range-checked against the buffer's size, so no clamp of the offset is needed to stay
+// inside the tensor).  No "memory" clobber: the transfer is asynchronous anyway (what orders it against the reads
+// of the tile it fills are the caller's explicit wait and barrier, which the compiler does not move a volatile
+// asm across), and without the clobber the compiler may keep scheduling LDS reads of OTHER buffers across it.
+__device__ __forceinline__ void load_buffer_to_lds_16B(i32x4 buffer, uint32_t byte_offset, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_wave_base), "v"(byte_offset), "s"(buffer)
+                 );
+}
+
 // LDS byte address of a __shared__ object, made wave-uniform
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)CHIPMUNK_LDS_PTR(p));
