@@ -416,14 +416,22 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     };
     // One of the E/16 transfers that fill buffer half `half` with the tiles whose columns are in colv: piece j is
     // the K (j even) or V (j odd) part of load i = (j/2) % NI of tile s = j / (2 NI).
+    uint32_t goff[kTilesPerStep][NI];   // byte offset of the lane's chunk inside the head's K (and V) matrix
+    auto gather_offsets = [&]() {       // from the column numbers that have landed: once per step, ahead of the products
+#pragma unroll
+        for (int s = 0; s < kTilesPerStep; s++)
+#pragma unroll
+            for (int i = 0; i < NI; i++) {
+                goff[s][i] = (uint32_t)colv[s][i] * ROWB + chunk_off[i];
+                asm volatile("" : "+v"(goff[s][i]));   // formed here, not again in front of every transfer
+            }
+    };
     auto gather_piece = [&](auto half_c, int j) {
         constexpr int half = decltype(half_c)::value;
         const int s = j / (2 * NI), i = (j / 2) % NI;
-        // byte offset of this lane's chunk inside the head's K (and V) matrix
-        const uint32_t goff = (uint32_t)colv[s][i] * ROWB + chunk_off[i];
         const uint32_t dst = lds0 + (uint32_t)((half * kTilesPerStep + s) * STAGE + i * NWAVES * 1024);
-        if (j & 1) load_buffer_to_lds_16B(vbuf, goff, dst + TILE);
-        else load_buffer_to_lds_16B(kbuf, goff, dst);
+        if (j & 1) load_buffer_to_lds_16B(vbuf, goff[s][i], dst + TILE);
+        else load_buffer_to_lds_16B(kbuf, goff[s][i], dst);
     };
     static_assert(kTilesPerStep * NI * 2 == E / 16, "one transfer per group of score products");
 
@@ -434,6 +442,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     wait_all_memory();
 
     // first step in flight; columns of the second step requested
+    gather_offsets();
 #pragma unroll
     for (int j = 0; j < E / 16; j++) gather_piece(std::integral_constant<int, 0>{}, j);
     load_cols();
@@ -447,6 +456,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         constexpr int half = decltype(half_c)::value;
         wait_all_memory();
         __syncthreads();  // this step's tiles have landed for every wave; the other half is free to refill
+        gather_offsets();
         if (FUSED && t > 0) flush_column_sums(t - kTilesPerStep);
 #pragma unroll
         for (int s = 0; s < kTilesPerStep; s++) {
