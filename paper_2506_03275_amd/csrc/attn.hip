@@ -67,8 +67,8 @@ struct AttnState {
     f32x4 O[E / 16][NQB];
     f32x4 L[NQB];     // softmax denominator, accumulated by the MFMA against a row of ones
     bf16x8 Q[E / 32][NQB];
-    f32x4 negm[NQB];  // -m in all four registers: the C operand that starts every score accumulation
-    float m[NQB];     // running reference max, in units of the raw scores <q,k>
+    f32x4 negm[NQB];  // -m in all four registers (m: the running reference max, in units of the raw scores <q,k>; it
+                      // is replaced by the first tile's row maximum): the C operand that starts every score accumulation
 };
 
 // The work on one tile of 32 selected key rows is split in three pieces so that
@@ -91,22 +91,22 @@ __device__ __forceinline__ short4v lds_read_tr16_at(uint32_t addr) {
 // between(j), j = 0 .. E/16 - 1, is called after the j-th group of NQB products: the kernel issues one of the next
 // step's tile transfers there, so that the transfers are spread over the products instead of queueing up in one
 // burst during which the wave issues nothing else.
-constexpr int kKPrefetch = 3;  // K operands requested ahead of the products that consume them
-
-template <int E, int NQB, typename Between>
+// K operands are requested KPF groups ahead of the products that consume them (2; the kernel with the column sums
+// of Alg. 4 has no registers to spare and keeps 1)
+template <int E, int NQB, int KPF, typename Between>
 __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<E, NQB>& st, const uint32_t (&kaddr)[E / 32],
                                             int tile_off, Between&& between) {
     constexpr int ROWB = E * 2;
     constexpr int NG = E / 16;   // groups of NQB products: group j = contraction slice j / 2, key rows 16 (j % 2) ..
     bf16x8 kop[NG];
 #pragma unroll
-    for (int j = 0; j < kKPrefetch; j++) kop[j] = lds_read_b128(kaddr[j / 2] + tile_off + (j % 2) * 16 * ROWB);
-    __builtin_amdgcn_sched_group_barrier(0x100, kKPrefetch, 0);  // the LDS reads lead the block
+    for (int j = 0; j < KPF; j++) kop[j] = lds_read_b128(kaddr[j / 2] + tile_off + (j % 2) * 16 * ROWB);
+    __builtin_amdgcn_sched_group_barrier(0x100, KPF, 0);  // the LDS reads lead the block
 #pragma unroll
     for (int j = 0; j < NG; j++) {
         const int es = j / 2, u = j % 2;
-        if (j + kKPrefetch < NG) {
-            const int jn = j + kKPrefetch;
+        if (j + KPF < NG) {
+            const int jn = j + KPF;
             kop[jn] = lds_read_b128(kaddr[jn / 2] + tile_off + (jn % 2) * 16 * ROWB);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
@@ -118,14 +118,25 @@ __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<
     }
 }
 
-// The last tile of a unit: rows at or beyond `count` score -inf.
-template <int NQB>
-__device__ __forceinline__ void attn_mask_tail(f32x4 (&S)[2][NQB], int kv0, int count, int g) {
+// Inside a step (kTilesPerStep tiles) the rows of the LDS tiles are a fixed permutation of the step's list
+// positions: every lane of the gather fetches kTilesPerStep * NI consecutive positions (one vector load of column
+// numbers) and deals them out over the tiles.  Row q of tile s holds list position  step_base + list_pos(s, q).
+// The softmax does not care about the order; only the mask of the unit's last tiles and the column sums do.
+template <int E>
+__device__ __forceinline__ int list_pos_in_step(int s, int q) {
+    constexpr int NI = E / 64;                       // gather loads per wave, tile and matrix
+    constexpr int LANEROWS = kTileRows / NI;         // rows of a tile that one such load of every wave covers
+    return (q % LANEROWS) * (kTilesPerStep * NI) + s * NI + q / LANEROWS;
+}
+
+// The last tiles of a unit: rows whose list position is at or beyond `count` score -inf.
+template <int E, int NQB>
+__device__ __forceinline__ void attn_mask_tail(f32x4 (&S)[2][NQB], int step_base, int s, int count, int g) {
 #pragma unroll
     for (int u = 0; u < 2; u++)
 #pragma unroll
         for (int r = 0; r < 4; r++) {
-            bool dead = kv0 + u * 16 + 4 * g + r >= count;
+            bool dead = step_base + list_pos_in_step<E>(s, u * 16 + 4 * g + r) >= count;
 #pragma unroll
             for (int qb = 0; qb < NQB; qb++)
                 if (dead) S[u][qb][r] = -INFINITY;
@@ -157,8 +168,8 @@ __device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, f32x4 (&S
             float d = rows4_max(mx[qb]);             // the tile's row maximum relative to the reference
             float up = first ? d : fmaxf(d, 0.f);    // the reference only rises, except when it is first set
             float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-up * sl2);   // O and L are still zero on the first tile
-            st.m[qb] += up;
-            st.negm[qb] = f32x4{-st.m[qb], -st.m[qb], -st.m[qb], -st.m[qb]};
+            const float nm = st.negm[qb][0] - up;
+            st.negm[qb] = f32x4{nm, nm, nm, nm};
             st.L[qb] *= alpha;
 #pragma unroll
             for (int eb = 0; eb < E / 16; eb++) st.O[eb][qb] *= alpha;
@@ -174,7 +185,7 @@ __device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, f32x4 (&S
 // The transposing V reads do not depend on the probabilities: the first kVPrefetch
 // operands are requested before the exponentials, the rest kVPrefetch steps ahead
 // of the MFMAs that consume them, so LDS latency stays off the MFMA chain.
-constexpr int kVPrefetch = 3;
+constexpr int kVPrefetch = 3;        // (2 in the kernel with the column sums)
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x) {  // x of the lane that the DPP control CTRL names
@@ -200,7 +211,7 @@ __device__ __forceinline__ void row16_sums_to_lds(const float (&acc)[8], float* 
 // COLSUM (Alg. 4): also the tile's column sums with given normalisers.  The weight of (key, query) there is
 // exp2(score * sl2 - prev_m2) / prev_l = p * wq, with p the probability formed here against the running
 // reference st.m and wq = exp2(st.m * sl2 + off) per query, off = -prev_m2 - log2(prev_l) (-inf: no such query).
-template <int E, int NQB, bool COLSUM = false>
+template <int E, int NQB, bool COLSUM = false, int VPF = kVPrefetch>
 __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const f32x4 (&S)[2][NQB],
                                                     const uint32_t (&vaddr)[E / 16], int tile_off, float sl2, bf16x8 ones,
                                                     const float* off = nullptr, float* part = nullptr, int g = 0,
@@ -210,11 +221,11 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
     typedef __attribute__((ext_vector_type(8))) short short8v;
     short4v vlo[NEB], vhi[NEB];
 #pragma unroll
-    for (int eb = 0; eb < kVPrefetch; eb++) {
+    for (int eb = 0; eb < VPF; eb++) {
         vlo[eb] = lds_read_tr16_at(vaddr[eb] + tile_off);
         vhi[eb] = lds_read_tr16_at(vaddr[eb] + tile_off + 16 * ROWB);
     }
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kVPrefetch, 0);  // the LDS reads lead the block
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * VPF, 0);  // the LDS reads lead the block
     bf16x8 pop[NQB];
     float acc[8];
 #pragma unroll
@@ -227,7 +238,7 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
                 pv[u * 4 + r] = __builtin_amdgcn_exp2f(S[u][qb][r] * sl2);
         if (COLSUM) {
             // the cap keeps wq finite, so that a zero probability times it stays zero
-            const float wq = __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(st.m[qb], sl2, off[qb]), 126.f));
+            const float wq = __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(-st.negm[qb][0], sl2, off[qb]), 126.f));
 #pragma unroll
             for (int j = 0; j < 8; j++) acc[j] = qb == 0 ? pv[j] * wq : __builtin_fmaf(pv[j], wq, acc[j]);
         }
@@ -244,9 +255,9 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
     __builtin_amdgcn_sched_group_barrier(0x008, NQB, 0);
 #pragma unroll
     for (int eb = 0; eb < NEB; eb++) {
-        if (eb + kVPrefetch < NEB) {
-            vlo[eb + kVPrefetch] = lds_read_tr16_at(vaddr[eb + kVPrefetch] + tile_off);
-            vhi[eb + kVPrefetch] = lds_read_tr16_at(vaddr[eb + kVPrefetch] + tile_off + 16 * ROWB);
+        if (eb + VPF < NEB) {
+            vlo[eb + VPF] = lds_read_tr16_at(vaddr[eb + VPF] + tile_off);
+            vhi[eb + VPF] = lds_read_tr16_at(vaddr[eb + VPF] + tile_off + 16 * ROWB);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
         short8v both = __builtin_shufflevector(vlo[eb], vhi[eb], 0, 1, 2, 3, 4, 5, 6, 7);
@@ -309,7 +320,6 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     AttnState<E, NQB> st;
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
-        st.m[qb] = 0.f;  // replaced by the first tile's row maximum
         st.negm[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.L[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -345,7 +355,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             const float* part = s_part + ((tile0 / kTilesPerStep) & 1) * (NWAVES * kTilesPerStep * kTileRows);
             float v = 0.f;
             for (int ww = 0; ww < active_waves; ww++) v += part[ww * (kTilesPerStep * kTileRows) + tid];
-            const int j = tile0 * kTileRows + tid;
+            const int j = tile0 * kTileRows + list_pos_in_step<E>(tid / kTileRows, tid % kTileRows);
             if (j < p.N) colsum_row[j] = v;
         }
     };
@@ -375,7 +385,9 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     // and therefore fetches the logical chunk  position ^ swizzle(row).
     const int sel = lane / CH;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
-    const int ntiles = (count + kTileRows - 1) / kTileRows;
+    // whole steps: the rows of a step's tiles interleave the step's list positions (list_pos_in_step), so the last
+    // step runs all its tiles, masked
+    const int ntiles = (count + kTilesPerStep * kTileRows - 1) / (kTilesPerStep * kTileRows) * kTilesPerStep;
     uint32_t chunk_off[NI];  // byte offset of the lane's chunk inside the row it fetches
 #pragma unroll
     for (int i = 0; i < NI; i++) chunk_off[i] = (uint32_t)(((lane % CH) ^ swizzle<E>((i * NWAVES + w) * RPI + sel)) * 16);
@@ -387,44 +399,65 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const i32x4 kbuf = raw_buffer_words(kh, (uint32_t)p.N * ROWB);
     const i32x4 vbuf = raw_buffer_words(vh, (uint32_t)p.N * ROWB);
     const int32_t* idxg = p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
+    // two views of the unit's list: its whole row (positions below k_stride: the vector loads of the steps that lie
+    // inside the list) and the part below count (a position at or beyond count reads as 0: the list's last step)
+    const __amdgpu_buffer_rsrc_t ibuf_row = raw_buffer(idxg, idxg ? (uint32_t)p.k_stride * 4u : 0u);
     const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(idxg, idxg ? (uint32_t)count * 4u : 0u);
 
-    // Every lane fetches the selected column of the tile row it fills, one step ahead of
-    // the gather that uses it: the loads are issued behind that step's tile transfers and
-    // have landed, like those, when the next step starts with its wait for all memory.
-    // colv[s][i] belongs to row (i*NWAVES+w)*RPI + sel of the s-th tile of a step; in the list
-    // that is position  step's first column + s*kTileRows + i*NWAVES*RPI + (w*RPI + sel): the
-    // last term is the lane's own (next_pos), the others are immediates of the loads.
-    int colv[kTilesPerStep][NI];
-    int next_pos = w * RPI + sel;   // the lane's position in the list for (s = 0, i = 0) of the next step to load
-    int next_off = next_pos * 4;    // ... and its byte offset
+    // Every lane fetches the column numbers of the tile rows it fills, one step ahead of the gather that uses
+    // them: the load is issued behind that step's tile transfers and has landed, like those, when the next step
+    // starts with its wait for all memory.  A lane's kTilesPerStep * NI rows of a step hold consecutive list
+    // positions (list_pos_in_step), so one vector load brings them all.  The list's last step is the only one
+    // that can reach beyond count: its columns are fetched once, up front, entry by entry through the view that
+    // ends at count (colt), and the step before it (or the prologue) gathers from those.
+    constexpr int RPL = kTilesPerStep * NI;       // rows (= column numbers) per lane and step
+    static_assert(RPL == 4 || RPL == 2, "the column numbers of a step come as one 16- or 8-byte load per lane");
+    int colv[RPL], colt[RPL];
+    int next_pos = (w * RPI + sel) * RPL;         // the lane's first list position in the next step to load
+    if constexpr (!FUSED) {
+        const int last_pos = (ntiles / kTilesPerStep - 1) * (kTilesPerStep * kTileRows) + next_pos;
+#pragma unroll
+        for (int j = 0; j < RPL; j++)
+            colt[j] = idxg ? __builtin_amdgcn_raw_buffer_load_b32(ibuf, (last_pos + j) * 4, 0, 0) : min(last_pos + j, p.N - 1);
+    }
     auto load_cols = [&]() {
+        if constexpr (FUSED) return;   // gather_offsets forms the columns from the positions
         if (idxg) {
+            if constexpr (RPL == 4) {
+                const u32x4 c4 = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ibuf_row, next_pos * 4, 0, 0));
 #pragma unroll
-            for (int s = 0; s < kTilesPerStep; s++)
+                for (int j = 0; j < RPL; j++) colv[j] = (int)c4[j];
+            } else {
+                const u32x2 c2 = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(ibuf_row, next_pos * 4, 0, 0));
 #pragma unroll
-                for (int i = 0; i < NI; i++)
-                    colv[s][i] = __builtin_amdgcn_raw_buffer_load_b32(ibuf, next_off + (s * kTileRows + i * NWAVES * RPI) * 4, 0, 0);
+                for (int j = 0; j < RPL; j++) colv[j] = (int)c2[j];
+            }
         } else {  // dense: column = position
 #pragma unroll
-            for (int s = 0; s < kTilesPerStep; s++)
-#pragma unroll
-                for (int i = 0; i < NI; i++) colv[s][i] = min(next_pos + s * kTileRows + i * NWAVES * RPI, p.N - 1);
+            for (int j = 0; j < RPL; j++) colv[j] = min(next_pos + j, p.N - 1);
         }
         next_pos += kTilesPerStep * kTileRows;
-        next_off += kTilesPerStep * kTileRows * 4;
     };
     // One of the E/16 transfers that fill buffer half `half` with the tiles whose columns are in colv: piece j is
     // the K (j even) or V (j odd) part of load i = (j/2) % NI of tile s = j / (2 NI).
     uint32_t goff[kTilesPerStep][NI];   // byte offset of the lane's chunk inside the head's K (and V) matrix
-    auto gather_offsets = [&]() {       // from the column numbers that have landed: once per step, ahead of the products
+    // from the column numbers that have landed: once per step, ahead of the products; `last`: the step to gather
+    // is the list's last one
+    int gather_pos = (w * RPI + sel) * RPL;       // FUSED: the lane's first list position in the next step to gather
+    auto gather_offsets = [&](bool last) {
 #pragma unroll
         for (int s = 0; s < kTilesPerStep; s++)
 #pragma unroll
             for (int i = 0; i < NI; i++) {
-                goff[s][i] = (uint32_t)colv[s][i] * ROWB + chunk_off[i];
-                asm volatile("" : "+v"(goff[s][i]));   // formed here, not again in front of every transfer
+                int col;
+                if constexpr (FUSED) col = min(gather_pos + s * NI + i, p.N - 1);   // always dense: column = position
+                else col = last ? colt[s * NI + i] : colv[s * NI + i];
+                goff[s][i] = (uint32_t)col * ROWB + chunk_off[i];
+                // formed here, not again in front of every transfer (the kernel with the column sums has no
+                // registers for that and lets the compiler form them where it likes)
+                if constexpr (!FUSED) asm volatile("" : "+v"(goff[s][i]));
             }
+        gather_pos += kTilesPerStep * kTileRows;
     };
     auto gather_piece = [&](auto half_c, int j) {
         constexpr int half = decltype(half_c)::value;
@@ -442,7 +475,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     wait_all_memory();
 
     // first step in flight; columns of the second step requested
-    gather_offsets();
+    gather_offsets(ntiles <= kTilesPerStep);
 #pragma unroll
     for (int j = 0; j < E / 16; j++) gather_piece(std::integral_constant<int, 0>{}, j);
     load_cols();
@@ -456,23 +489,22 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         constexpr int half = decltype(half_c)::value;
         wait_all_memory();
         __syncthreads();  // this step's tiles have landed for every wave; the other half is free to refill
-        gather_offsets();
+        gather_offsets(t + 2 * kTilesPerStep >= ntiles);
         if (FUSED && t > 0) flush_column_sums(t - kTilesPerStep);
 #pragma unroll
         for (int s = 0; s < kTilesPerStep; s++) {
             const int tile_off = (half * kTilesPerStep + s) * STAGE;   // a constant once the loop over s is unrolled
             f32x4 S[2][NQB];
             if (s == 0) {
-                attn_scores<E, NQB>(S, st, kaddr, tile_off,
+                attn_scores<E, NQB, FUSED ? 1 : 2>(S, st, kaddr, tile_off,
                                     [&](int j) { gather_piece(std::integral_constant<int, half ^ 1>{}, j); });
                 load_cols();
             } else {
-                if (t + s >= ntiles) break;
-                attn_scores<E, NQB>(S, st, kaddr, tile_off, [](int) {});
+                attn_scores<E, NQB, FUSED ? 1 : 2>(S, st, kaddr, tile_off, [](int) {});
             }
-            if (t + s + 1 >= ntiles) attn_mask_tail<NQB>(S, (t + s) * kTileRows, count, g);
+            if (t + kTilesPerStep >= ntiles) attn_mask_tail<E, NQB>(S, t * kTileRows, s, count, g);
             attn_update_max<E, NQB>(st, S, t + s == 0, p.sl2, slack);
-            attn_weights_and_pv<E, NQB, FUSED>(st, S, vaddr, tile_off + TILE, p.sl2, ones, off,
+            attn_weights_and_pv<E, NQB, FUSED, FUSED ? 1 : kVPrefetch>(st, S, vaddr, tile_off + TILE, p.sl2, ones, off,
                                                s_part + ((half * NWAVES + w) * kTilesPerStep + s) * kTileRows, g, l16);
         }
     };
@@ -504,7 +536,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         for (int eb = 0; eb < E / 16; eb++) bv[eb] = *reinterpret_cast<const u32x2*>(base_src + row_off + eb * 16);
         if (qrow < rows_valid) {
             if (p.row_m && g == 0) {
-                p.row_m[bh * p.N + row0 + qrow] = st.m[qb] * (p.sl2 * 0.6931471805599453f);
+                p.row_m[bh * p.N + row0 + qrow] = -st.negm[qb][0] * (p.sl2 * 0.6931471805599453f);
                 p.row_l[bh * p.N + row0 + qrow] = ltot;
             }
 #pragma unroll
