@@ -546,17 +546,42 @@ def main():
         ib, cb = si.block_indices(R, st["N"], st["k_a"], 128, args.seed, dev)
         kinds["blocks_of_128_columns"] = (ib.view(st["B"], st["H"], st["NB"], -1), cb.view(st["B"], st["H"], st["NB"]))
         extra["attn_index_structures"] = {}
-        for kind, (idx, cnt) in kinds.items():
+
+        def time_launch(fn):
             t = Timer()
             for i in range(4):
                 a, b = t.span("k") if i else Timer().span("warm")
                 a.record()
-                cm.attn_sparse_delta(st["q"], st["k"], st["v"], idx, cnt, st["o_cache_attn"], st["o_attn"], st["c"],
-                                     st["scale"], 1.0)
+                fn()
                 b.record()
             torch.cuda.synchronize()
-            ms = t.mean_ms("k")
+            return t.mean_ms("k")
+
+        for kind, (idx, cnt) in kinds.items():
+            ms = time_launch(lambda: cm.attn_sparse_delta(st["q"], st["k"], st["v"], idx, cnt, st["o_cache_attn"],
+                                                          st["o_attn"], st["c"], st["scale"], 1.0))
             extra["attn_index_structures"][kind] = {"ms": ms, "useful_tflops": fl_attn / (ms * 1e-3) / 1e12}
+        # the [c, 128] block pattern of Table 2 on the kernel that walks block lists (no per-column index), beside
+        # the column kernel on a list of the same length
+        n_blocks = max(1, st["k_a"] // cm.ATTN_BLOCK_COLUMNS)
+        kept = n_blocks * cm.ATTN_BLOCK_COLUMNS
+        keys = torch.rand((R, -(-st["N"] // cm.ATTN_BLOCK_COLUMNS)), device=dev, generator=si.generator(args.seed + 17, dev))
+        blocks = keys.argsort(dim=1)[:, :n_blocks].sort(dim=1).values.to(torch.int32).contiguous()
+        bcnt = torch.full((R,), n_blocks, dtype=torch.int32, device=dev)
+        fl_blocks = 4.0 * st["E"] * st["H"] * st["B"] * st["N"] * kept      # upper bound: the last block may be cut at N
+        ms = time_launch(lambda: cm.attn_block_sparse_delta(st["q"], st["k"], st["v"],
+                                                            blocks.view(st["B"], st["H"], st["NB"], -1),
+                                                            bcnt.view(st["B"], st["H"], st["NB"]), st["o_cache_attn"],
+                                                            st["o_attn"], st["c"], st["scale"], 1.0))
+        extra["attn_index_structures"]["block_list_kernel_c_x_128"] = {
+            "ms": ms, "blocks_per_chunk": n_blocks, "columns_kept": kept, "useful_tflops": fl_blocks / (ms * 1e-3) / 1e12}
+        iu2, cu2 = si.uniform_indices(R, st["N"], kept, args.seed + 1, dev)
+        ms = time_launch(lambda: cm.attn_sparse_delta(st["q"], st["k"], st["v"], iu2.view(st["B"], st["H"], st["NB"], -1),
+                                                      cu2.view(st["B"], st["H"], st["NB"]), st["o_cache_attn"], st["o_attn"],
+                                                      st["c"], st["scale"], 1.0))
+        extra["attn_index_structures"]["column_kernel_same_count_uniform"] = {
+            "ms": ms, "columns_kept": kept, "useful_tflops": fl_blocks / (ms * 1e-3) / 1e12}
+        del blocks, iu2
         del kinds, iu, ib
 
     if not args.no_dense:

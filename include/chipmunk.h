@@ -95,6 +95,22 @@ int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t* k, const u
                                    int B, int H, int N, int E, int c, int k_stride,
                                    float softmax_scale, float o_scale, void* stream);
 
+/* Block-sparse delta attention: the [c, 128] block pattern that Table 2 sets beside the [c, 1] columns
+ * (Sec. 3.2.1).  blocks[b,h,i,0:block_counts[b,h,i]] names blocks of CHIPMUNK_ATTN_BLOCK_COLUMNS consecutive
+ * key columns (block j = columns 128 j .. 128 j + 127, cut at N); the result is that of
+ * chipmunk_attn_sparse_delta on the list of all columns of those blocks:
+ *   out[n] = base[n] + o_scale * softmax_{j in the selected blocks}(softmax_scale * <q[n],k[j]>) v[j].
+ * The kernel fetches each block's K and V rows as contiguous runs, with no per-column index.  A block listed
+ * twice counts twice (the list is taken as given); every entry below its row's count must lie in
+ * [0, ceil(N/128)).  blocks: [B,H,NB,kb_stride] int32; block_counts: [B,H,NB] int32, each in [0, kb_stride];
+ * block_counts == 0 gives out = base.  Other arguments and limits as for chipmunk_attn_sparse_delta. */
+#define CHIPMUNK_ATTN_BLOCK_COLUMNS 128
+int32_t chipmunk_attn_block_sparse_delta(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                                         const int32_t* blocks, const int32_t* block_counts,
+                                         const uint16_t* base, uint16_t* out,
+                                         int B, int H, int N, int E, int c, int kb_stride,
+                                         float softmax_scale, float o_scale, void* stream);
+
 /* Workspace bytes of chipmunk_attn_dense when column sums are requested (0 on bad arguments). */
 size_t chipmunk_attn_dense_workspace_bytes(int B, int H, int N);
 

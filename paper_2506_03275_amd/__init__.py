@@ -30,6 +30,7 @@ _SIGNATURES = {
     "chipmunk_topk_cols": ([_c_ptr, _c_ptr, _c_int, _c_int, _c_i64, _c_int, _c_ptr, _c_ptr, _c_int, _c_ptr],
                            ctypes.c_int32),
     "chipmunk_attn_sparse_delta": ([_c_ptr] * 7 + [_c_int] * 6 + [_c_f32, _c_f32, _c_ptr], ctypes.c_int32),
+    "chipmunk_attn_block_sparse_delta": ([_c_ptr] * 7 + [_c_int] * 6 + [_c_f32, _c_f32, _c_ptr], ctypes.c_int32),
     "chipmunk_attn_dense_workspace_bytes": ([_c_int] * 3, _c_size),
     "chipmunk_attn_dense": ([_c_ptr] * 5 + [_c_i64] + [_c_int] * 5 + [_c_f32, _c_ptr, _c_size, _c_ptr],
                             ctypes.c_int32),
@@ -149,6 +150,22 @@ def attn_sparse_delta(q, k, v, idx, counts, base, out, c, softmax_scale, o_scale
                                              _ptr(base, bf, "base"), _ptr(out, bf, "out"), B, H, N, E, c,
                                              k_stride, float(softmax_scale), float(o_scale), _stream()),
            "chipmunk_attn_sparse_delta")
+
+
+ATTN_BLOCK_COLUMNS = 128
+
+
+def attn_block_sparse_delta(q, k, v, blocks, block_counts, base, out, c, softmax_scale, o_scale):
+    """q,k,v,base,out: bf16 [B,H,N,E]; blocks: int32 [B,H,NB,kb_stride] (numbers of 128-column key blocks);
+    block_counts: int32 [B,H,NB]."""
+    B, H, N, E = q.shape
+    bf = torch.bfloat16
+    _check(load().chipmunk_attn_block_sparse_delta(_ptr(q, bf, "q"), _ptr(k, bf, "k"), _ptr(v, bf, "v"),
+                                                   _ptr(blocks, torch.int32, "blocks"),
+                                                   _ptr(block_counts, torch.int32, "block_counts"),
+                                                   _ptr(base, bf, "base"), _ptr(out, bf, "out"), B, H, N, E, c,
+                                                   blocks.shape[-1], float(softmax_scale), float(o_scale), _stream()),
+           "chipmunk_attn_block_sparse_delta")
 
 
 def attn_dense_workspace_bytes(B, H, N):

@@ -269,10 +269,20 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
     }
 }
 
+constexpr int kBlockColumns = CHIPMUNK_ATTN_BLOCK_COLUMNS;   // key columns per entry of a block list
+static_assert(kBlockColumns % (kTilesPerStep * kTileRows) == 0, "a step never straddles two blocks");
+
+// What the kernel walks.  kColumnList: the unit's list of columns (or, without a list, every column: dense).
+// kFusedDense: every column, and the column sums of Alg. 4 are formed from the same score tiles.  kBlockList: the
+// unit's list names blocks of kBlockColumns consecutive columns (the [c, 128] block sparsity of Table 2); the list
+// positions are the blocks' columns in order, so the rows of a step are one contiguous run of K and V.
+enum AttnMode { kColumnList = 0, kFusedDense = 1, kBlockList = 2 };
+
 // NWAVES waves per workgroup, each owning NQB blocks of 16 queries: c = 16 * NQB * NWAVES.
-// FUSED (dense launches only: no index list): the column sums of Alg. 4 are formed from the same score tiles.
-template <int E, int NQB, int NWAVES, bool FUSED = false>
+template <int E, int NQB, int NWAVES, int MODE = kColumnList>
 __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_delta_kernel(AttnParams p) {
+    constexpr bool FUSED = MODE == kFusedDense;
+    constexpr bool BLOCKS = MODE == kBlockList;
     constexpr int ROWB = E * 2;           // bytes per K/V row
     constexpr int CH = ROWB / 16;         // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // rows covered by one wave-wide 16-byte load
@@ -299,7 +309,13 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     const int rows_valid = min(p.c, p.N - row0);
     // Contents of counts and idx are the caller's precondition; they are clamped all the same so that a bad
     // entry reads a wrong row instead of leaving the tensors.
-    const int count = __builtin_amdgcn_readfirstlane(p.counts ? min(p.counts[unit], p.k_stride) : p.N);
+    // (block lists: counts and k_stride are in blocks; `count` is in list positions = columns all the same)
+    const int entries = __builtin_amdgcn_readfirstlane(p.counts ? min(p.counts[unit], p.k_stride) : p.N);
+    int count = BLOCKS ? entries * kBlockColumns : entries;
+    // The length is hidden from the compiler's value tracking: knowing that a block list's length is a multiple
+    // of two steps, it fuses the two copies of the step below into one scheduling region and then needs far
+    // more registers than there are (hundreds of bytes of spills in the main loop).
+    asm volatile("" : "+s"(count));
 
     const int64_t head_off = bh * (int64_t)p.N * E;
     const uint16_t* qh = p.q + head_off;
@@ -402,7 +418,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     // two views of the unit's list: its whole row (positions below k_stride: the vector loads of the steps that lie
     // inside the list) and the part below count (a position at or beyond count reads as 0: the list's last step)
     const __amdgpu_buffer_rsrc_t ibuf_row = raw_buffer(idxg, idxg ? (uint32_t)p.k_stride * 4u : 0u);
-    const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(idxg, idxg ? (uint32_t)count * 4u : 0u);
+    const __amdgpu_buffer_rsrc_t ibuf = raw_buffer(idxg, idxg ? (uint32_t)entries * 4u : 0u);
 
     // Every lane fetches the column numbers of the tile rows it fills, one step ahead of the gather that uses
     // them: the load is issued behind that step's tile transfers and has landed, like those, when the next step
@@ -414,14 +430,21 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     static_assert(RPL == 4 || RPL == 2, "the column numbers of a step come as one 16- or 8-byte load per lane");
     int colv[RPL], colt[RPL];
     int next_pos = (w * RPI + sel) * RPL;         // the lane's first list position in the next step to load
-    if constexpr (!FUSED) {
+    if constexpr (MODE == kColumnList) {
         const int last_pos = (ntiles / kTilesPerStep - 1) * (kTilesPerStep * kTileRows) + next_pos;
 #pragma unroll
         for (int j = 0; j < RPL; j++)
             colt[j] = idxg ? __builtin_amdgcn_raw_buffer_load_b32(ibuf, (last_pos + j) * 4, 0, 0) : min(last_pos + j, p.N - 1);
     }
+    int blockv = 0;                               // BLOCKS: the block that holds the next step to gather (the same in every lane)
+    int block_now = 0, block_next = 0;            // BLOCKS: first column of the block of the step in work / of the next step
     auto load_cols = [&]() {
         if constexpr (FUSED) return;   // gather_offsets forms the columns from the positions
+        if constexpr (BLOCKS) {        // one list entry serves kBlockColumns positions; past the list's end it reads as block 0
+            blockv = __builtin_amdgcn_raw_buffer_load_b32(ibuf, (next_pos / kBlockColumns) * 4, 0, 0);
+            next_pos += kTilesPerStep * kTileRows;
+            return;
+        }
         if (idxg) {
             if constexpr (RPL == 4) {
                 const u32x4 c4 = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ibuf_row, next_pos * 4, 0, 0));
@@ -451,6 +474,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             for (int i = 0; i < NI; i++) {
                 int col;
                 if constexpr (FUSED) col = min(gather_pos + s * NI + i, p.N - 1);   // always dense: column = position
+                else if constexpr (BLOCKS) col = min(blockv * kBlockColumns + (gather_pos % kBlockColumns) + s * NI + i, p.N - 1);
                 else col = last ? colt[s * NI + i] : colv[s * NI + i];
                 goff[s][i] = (uint32_t)col * ROWB + chunk_off[i];
                 // formed here, not again in front of every transfer (the kernel with the column sums has no
@@ -458,6 +482,10 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
                 if constexpr (!FUSED) asm volatile("" : "+v"(goff[s][i]));
             }
         gather_pos += kTilesPerStep * kTileRows;
+        if constexpr (BLOCKS) {
+            block_now = block_next;
+            block_next = __builtin_amdgcn_readfirstlane(blockv) * kBlockColumns;
+        }
     };
     auto gather_piece = [&](auto half_c, int j) {
         constexpr int half = decltype(half_c)::value;
@@ -502,7 +530,12 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             } else {
                 attn_scores<E, NQB, FUSED ? 1 : 2>(S, st, kaddr, tile_off, [](int) {});
             }
-            if (t + kTilesPerStep >= ntiles) attn_mask_tail<E, NQB>(S, t * kTileRows, s, count, g);
+            if constexpr (BLOCKS) {   // only the sequence's last block can reach beyond N; it may stand anywhere in the list
+                const int col0 = block_now + (t * kTileRows) % kBlockColumns;
+                if (col0 + kTilesPerStep * kTileRows > p.N) attn_mask_tail<E, NQB>(S, col0, s, p.N, g);
+            } else {
+                if (t + kTilesPerStep >= ntiles) attn_mask_tail<E, NQB>(S, t * kTileRows, s, count, g);
+            }
             attn_update_max<E, NQB>(st, S, t + s == 0, p.sl2, slack);
             attn_weights_and_pv<E, NQB, FUSED, FUSED ? 1 : kVPrefetch>(st, S, vaddr, tile_off + TILE, p.sl2, ones, off,
                                                s_part + ((half * NWAVES + w) * kTilesPerStep + s) * kTileRows, g, l16);
@@ -675,15 +708,15 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(ColsumParams p) {
     flush(ntiles - 1);
 }
 
-template <int E, int NQB, int NWAVES, bool FUSED = false>
+template <int E, int NQB, int NWAVES, int MODE = kColumnList>
 static int32_t launch_attn_variant(const AttnParams& p, int64_t units, hipStream_t s) {
     constexpr int lds = kStages * 2 * kTileRows * E * 2;
     // set at every launch: the attribute is kept per device, and a flag remembered here would be neither
     // per device nor safe between host threads
-    if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>,
+    if (hipFuncSetAttribute((const void*)attn_sparse_delta_kernel<E, NQB, NWAVES, MODE>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return CHIPMUNK_ERR_LAUNCH;
-    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB, NWAVES, FUSED>), dim3((unsigned)units), dim3(64 * NWAVES), lds, s, p);
+    hipLaunchKernelGGL((attn_sparse_delta_kernel<E, NQB, NWAVES, MODE>), dim3((unsigned)units), dim3(64 * NWAVES), lds, s, p);
     return launch_status();
 }
 
@@ -695,10 +728,17 @@ static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_
 }
 
 static int32_t launch_attn_fused(const AttnParams& p, int E, int64_t units, hipStream_t s) {
-    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4, true>(p, units, s);
-    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4, true>(p, units, s);
-    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4, true>(p, units, s);
-    return launch_attn_variant<64, 2, 4, true>(p, units, s);
+    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4, kFusedDense>(p, units, s);
+    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4, kFusedDense>(p, units, s);
+    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4, kFusedDense>(p, units, s);
+    return launch_attn_variant<64, 2, 4, kFusedDense>(p, units, s);
+}
+
+static int32_t launch_attn_blocks(const AttnParams& p, int E, int64_t units, hipStream_t s) {
+    if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4, kBlockList>(p, units, s);
+    if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4, kBlockList>(p, units, s);
+    if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4, kBlockList>(p, units, s);
+    return launch_attn_variant<64, 2, 4, kBlockList>(p, units, s);
 }
 
 static int32_t launch_colsum(const ColsumParams& cp, int E, int64_t units, hipStream_t s) {
@@ -748,6 +788,30 @@ extern "C" int32_t chipmunk_attn_sparse_delta(const uint16_t* q, const uint16_t*
     p.sl2 = softmax_scale * 1.4426950408889634f;
     p.o_scale = o_scale;
     return launch_attn(p, E, units, (hipStream_t)stream);
+}
+
+extern "C" int32_t chipmunk_attn_block_sparse_delta(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                                                    const int32_t* blocks, const int32_t* block_counts,
+                                                    const uint16_t* base, uint16_t* out, int B, int H, int N,
+                                                    int E, int c, int kb_stride, float softmax_scale,
+                                                    float o_scale, void* stream) {
+    if (!q || !k || !v || !out || !blocks || !block_counts || !base) return CHIPMUNK_ERR_NULL;
+    if (kb_stride < 0 || !is_finite_scalar(o_scale)) return CHIPMUNK_ERR_SHAPE;
+    if (int32_t st = check_attn_shapes(B, H, N, E, c, softmax_scale)) return st;
+    if ((int64_t)kb_stride * kBlockColumns > 0x7fffffffLL) return CHIPMUNK_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(base) ||
+        (reinterpret_cast<uintptr_t>(blocks) & 3u) || (reinterpret_cast<uintptr_t>(block_counts) & 3u))
+        return CHIPMUNK_ERR_ALIGN;
+    int NB = (N + c - 1) / c;
+    int64_t units = (int64_t)B * H * NB;
+    AttnParams p;
+    p.q = q; p.k = k; p.v = v; p.base = base; p.out = out; p.idx = blocks; p.counts = block_counts;
+    p.row_m = nullptr; p.row_l = nullptr;
+    p.prev_m = nullptr; p.prev_l = nullptr; p.colsum = nullptr; p.ld_colsum = 0;
+    p.N = N; p.NB = NB; p.c = c; p.k_stride = kb_stride;
+    p.sl2 = softmax_scale * 1.4426950408889634f;
+    p.o_scale = o_scale;
+    return launch_attn_blocks(p, E, units, (hipStream_t)stream);
 }
 
 extern "C" size_t chipmunk_attn_dense_workspace_bytes(int B, int H, int N) {

@@ -101,3 +101,36 @@ def mlp_indices(units, F, k, seed, device, ragged=False):
         if units > 1:
             counts[1] = k - 3
     return idx.contiguous(), counts
+
+
+def attn_block_lists(units, N, n_blocks, seed, device, ragged=False, block=128):
+    """blocks [units, n_blocks] int32: distinct 128-column key blocks per unit drawn uniformly, ascending;
+    block_counts [units].  With `ragged`: one empty list, one single block, one that ends with the sequence's last
+    (possibly partial) block, one that lists a block twice."""
+    total = -(-N // block)
+    g = si.generator(seed + 6000003, device)
+    keys = torch.rand((units, total), generator=g, device=device)
+    blocks = keys.argsort(dim=1)[:, :n_blocks].sort(dim=1).values.to(torch.int32).contiguous()
+    counts = torch.full((units,), n_blocks, dtype=torch.int32, device=device)
+    if ragged:
+        counts[0] = 0
+        counts[1 % units] = 1
+        blocks[-1, n_blocks - 1] = total - 1            # the last block of the sequence (cut at N)
+        if units > 2 and n_blocks > 1:
+            blocks[2, 1] = blocks[2, 0]                 # a repeated block counts twice
+    return blocks, counts
+
+
+def expand_block_lists(blocks, counts, N, block=128):
+    """The column lists Alg. 3 would be handed for these block lists: every column of every listed block, in list
+    order, cut at N.  Returns idx [units, k_stride] int32 (numpy), counts [units]."""
+    blocks = np.asarray(blocks)
+    counts = np.asarray(counts)
+    units, stride = blocks.shape
+    idx = np.zeros((units, max(stride * block, 1)), np.int32)
+    out_counts = np.zeros(units, np.int32)
+    for u in range(units):
+        cols = [c for b in blocks[u, :counts[u]] for c in range(int(b) * block, min(N, (int(b) + 1) * block))]
+        idx[u, :len(cols)] = cols
+        out_counts[u] = len(cols)
+    return idx, out_counts

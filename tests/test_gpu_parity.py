@@ -195,6 +195,74 @@ def test_attn_index_list_is_taken_as_given(cm, oracle, order, B, H, N, E, c, k):
         assert any(len(set(flat_i[u, :flat_c[u]])) < flat_c[u] for u in range(len(flat_c)))
 
 
+@pytest.mark.parametrize("B,H,N,E,c,n_blocks,ragged", [
+    (1, 2, 1024, 64, 128, 2, False),       # Tiny: 2 of 8 blocks
+    (1, 2, 1100, 128, 192, 3, True),       # the sequence's last block holds 76 columns; ragged last chunk
+    (2, 2, 700, 128, 128, 2, True),
+    (1, 1, 500, 64, 192, 4, True),         # every block (N < 4 * 128): dense, with the partial block
+    (1, 1, 100, 128, 192, 1, False),       # one partial block
+])
+def test_attn_block_sparse_delta_parity(cm, oracle, B, H, N, E, c, n_blocks, ragged):
+    """The [c, 128] block pattern of Table 2: the kernel that walks a list of 128-column key blocks against the
+    oracle's Alg. 3 on the list of all columns of those blocks."""
+    q, kk, v = recipes.attn_inputs(B, H, N, E, 4, DEV)
+    NB = -(-N // c)
+    units = B * H * NB
+    blocks, bcounts = recipes.attn_block_lists(units, N, n_blocks, 4, DEV, ragged)
+    idxn, cntn = recipes.expand_block_lists(blocks.cpu().numpy(), bcounts.cpu().numpy(), N)
+    k_kept = max(int(cntn.max()), 1)
+    base = recipes.attn_base((B, H, N, E), k_kept, "delta", 4, DEV)
+    basen = si.np_f32(base).astype(np.float64)
+    scale = 1.0 / math.sqrt(E)
+    blocks4 = blocks.view(B, H, NB, n_blocks).contiguous()
+    bcounts3 = bcounts.view(B, H, NB).contiguous()
+    for o_scale in (1.0, -1.0):
+        out = torch.full_like(base, float("nan"))
+        cm.attn_block_sparse_delta(q, kk, v, blocks4, bcounts3, base, out, c, scale, o_scale)
+        ref = oracle.attn_sparse_delta(si.np_f32(q), si.np_f32(kk), si.np_f32(v), idxn.reshape(B, H, NB, -1),
+                                       cntn.reshape(B, H, NB), basen, c, scale, o_scale)
+        assert rel_err(si.np_f32(out), ref, ref - basen) <= REL_TOL
+    for b, h, i in np.argwhere(cntn.reshape(B, H, NB) == 0):       # nothing selected: the cache, bit for bit
+        assert torch.equal(out[b, h, i * c:(i + 1) * c], base[b, h, i * c:(i + 1) * c])
+    # the column-list kernel on the expanded lists gives the same result up to the order of the accumulation
+    idx_t = torch.from_numpy(idxn).to(DEV).view(B, H, NB, -1).contiguous()
+    cnt_t = torch.from_numpy(cntn).to(DEV).view(B, H, NB).contiguous()
+    out_cols = torch.empty_like(base)
+    cm.attn_sparse_delta(q, kk, v, idx_t, cnt_t, base, out_cols, c, scale, -1.0)
+    assert rel_err(si.np_f32(out_cols), si.np_f32(out).astype(np.float64), ref - basen) <= 1e-2
+
+
+def test_attn_block_sparse_hunyuan_shape_sampled_units(cm, oracle):
+    """The launch bench.py times for the block pattern (63 of 902 blocks per chunk, the kept count of 93 %
+    sparsity), sampled units against the oracle on a zero cache and on a cache at the delta's scale."""
+    cfg = si.CONFIGS["hunyuan"]
+    B, H, E, c = cfg["B"], cfg["H"], cfg["E"], cfg["c"]
+    N = si.config_tokens(cfg)
+    NB = -(-N // c)
+    n_blocks = si.kept(N, cfg["attn_keep"]) // cm.ATTN_BLOCK_COLUMNS
+    q, kk, v = recipes.attn_inputs(B, H, N, E, 0, DEV)
+    blocks, bcounts = recipes.attn_block_lists(B * H * NB, N, n_blocks, 0, DEV)
+    blocks4, bcounts3 = blocks.view(B, H, NB, n_blocks), bcounts.view(B, H, NB)
+    scale = 1.0 / math.sqrt(E)
+    rng = np.random.default_rng(1)
+    units = [(0, 0, 0), (B - 1, H - 1, NB - 1)] + [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(NB)))
+                                                     for _ in range(3)]
+    for mode in ("zero", "delta"):
+        base = recipes.attn_base((B, H, N, E), n_blocks * cm.ATTN_BLOCK_COLUMNS, mode, 0, DEV)
+        out = torch.empty_like(base)
+        cm.attn_block_sparse_delta(q, kk, v, blocks4, bcounts3, base, out, c, scale, 1.0)
+        torch.cuda.synchronize()
+        for b, h, i in units:
+            rows = slice(i * c, min(N, (i + 1) * c))
+            idxn, cntn = recipes.expand_block_lists(blocks4[b, h, i:i + 1].cpu().numpy(), bcounts3[b, h, i:i + 1].cpu().numpy(), N)
+            basen = si.np_f32(base[b:b + 1, h:h + 1, rows]).astype(np.float64)
+            ref = oracle.attn_sparse_delta(si.np_f32(q[b:b + 1, h:h + 1, rows]), si.np_f32(kk[b:b + 1, h:h + 1]),
+                                           si.np_f32(v[b:b + 1, h:h + 1]), idxn.reshape(1, 1, 1, -1), cntn.reshape(1, 1, 1),
+                                           basen, c, scale, 1.0)
+            assert rel_err(si.np_f32(out[b:b + 1, h:h + 1, rows]), ref, ref - basen) <= REL_TOL, (mode, b, h, i)
+        del base, out
+
+
 def test_attn_all_columns_equals_dense_and_cache_roundtrip(cm, oracle):
     """k = N reproduces dense attention; O_cache = O - Delta then O_cache + Delta returns O (Alg. 2)."""
     B, H, N, E, c = 1, 2, 520, 128, 192

@@ -58,6 +58,15 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     # K/V rows are addressed with 32-bit byte offsets inside a head: N * E * 2 must stay below 2^32
     assert f(a, a, a, a, a, a, a, 1, 1, 1 << 24, 128, 192, 8, 0.1, 1.0, None) == -2
     assert f(a, a, a, a, a, a, a, 1, 1, 1 << 25, 64, 192, 8, 0.1, 1.0, None) == -2
+    # block-sparse attention: the same checks as the column-list call
+    fb = lib.chipmunk_attn_block_sparse_delta
+    assert fb(a, a, a, None, a, a, a, 1, 1, 128, 128, 192, 8, 0.1, 1.0, None) == -1         # block list required
+    assert fb(a, a, a, a, a, None, a, 1, 1, 128, 128, 192, 8, 0.1, 1.0, None) == -1         # base required
+    assert fb(a, a, a, a, a, a, a, 1, 1, 128, 96, 192, 8, 0.1, 1.0, None) == -4             # E
+    assert fb(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, -1, 0.1, 1.0, None) == -2           # kb_stride
+    assert fb(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 1 << 25, 0.1, 1.0, None) == -2      # kb_stride * 128 overflows
+    assert fb(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, float("nan"), 1.0, None) == -2
+    assert fb(a, a, a, P(0x1002), a, a, a, 1, 1, 128, 128, 192, 8, 0.1, 1.0, None) == -3    # int32 alignment
     # top-k
     t = lib.chipmunk_topk_cols
     assert t(None, None, 1, 8, 8, 2, a, a, 2, None) == -1

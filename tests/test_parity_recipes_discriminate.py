@@ -69,6 +69,27 @@ def test_index_list_recipes_reject_a_short_delta(oracle, order, B, H, N, E, c, k
         assert rel_err(ref_dedup, ref, ref - basen) > REL_TOL
 
 
+@pytest.mark.parametrize("B,H,N,E,c,n_blocks,ragged", [
+    (1, 2, 1024, 64, 128, 2, False), (1, 2, 1100, 128, 192, 3, True), (2, 2, 700, 128, 128, 2, True),
+    (1, 1, 500, 64, 192, 4, True), (1, 1, 100, 128, 192, 1, False),
+])
+def test_block_list_recipes_reject_a_short_delta(oracle, B, H, N, E, c, n_blocks, ragged):
+    """Recipe of test_attn_block_sparse_delta_parity; and the expansion of a block list is what its text says."""
+    q, kk, v = recipes.attn_inputs(B, H, N, E, 4, CPU)
+    NB = -(-N // c)
+    blocks, bcounts = recipes.attn_block_lists(B * H * NB, N, n_blocks, 4, CPU, ragged)
+    idxn, cntn = recipes.expand_block_lists(blocks.numpy(), bcounts.numpy(), N)
+    for u in range(len(cntn)):                                        # every column of every listed block, cut at N
+        want = np.concatenate([np.arange(b * 128, min(N, (b + 1) * 128)) for b in blocks[u, :bcounts[u]].tolist()] or
+                              [np.zeros(0, np.int64)])
+        assert cntn[u] == len(want) and np.array_equal(idxn[u, :cntn[u]], want)
+    base = recipes.attn_base((B, H, N, E), max(int(cntn.max()), 1), "delta", 4, CPU)
+    basen = si.np_f32(base).astype(np.float64)
+    ref = oracle.attn_sparse_delta(si.np_f32(q), si.np_f32(kk), si.np_f32(v), idxn.reshape(B, H, NB, -1),
+                                   cntn.reshape(B, H, NB), basen, c, 1.0 / math.sqrt(E), 1.0)
+    assert _rejects(basen, ref)
+
+
 def test_roundtrip_recipe_rejects_a_short_delta(oracle):
     """Recipe of test_attn_all_columns_equals_dense_and_cache_roundtrip (cache = dense - delta, then + delta)."""
     B, H, N, E, c = 1, 2, 520, 128, 192
