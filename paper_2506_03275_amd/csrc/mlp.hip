@@ -152,14 +152,18 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     const uint16_t* xb = p.x + (int64_t)b * p.N * p.ldx;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
 
-    auto issue = [&](int kt, int stage) {
-        const uint16_t* xs = xb + kt * kBK;
-        const uint16_t* ws = p.w1 + (kt * kBK) % p.D;   // the scores GEMM walks w1's row twice (hi and lo halves of A)
-#pragma unroll
-        for (int i = 0; i < NIX; i++) load_global_to_lds_16B(xs, xoff[i], lds0 + stage * STAGE + i * 4096);
-#pragma unroll
-        for (int i = 0; i < NIW; i++) load_global_to_lds_16B(ws, woff[i], lds0 + stage * STAGE + XT + i * 4096);
+    // One of the NIX + NIW transfers that bring contraction step kt into buffer `stage`.  The main loop issues them
+    // one by one between its products: requested in one burst after the barrier they queue up in the memory
+    // pipeline while the wave issues nothing else.
+    auto issue_piece = [&](int kt, int stage, int j) {
+        if (j < NIX) {
+            load_global_to_lds_16B(xb + kt * kBK, xoff[j], lds0 + stage * STAGE + j * 4096);
+        } else {
+            const uint16_t* ws = p.w1 + (kt * kBK) % p.D;   // the scores GEMM walks w1's row twice (hi and lo halves of A)
+            load_global_to_lds_16B(ws, woff[j - NIX], lds0 + stage * STAGE + XT + (j - NIX) * 4096);
+        }
     };
+    static_assert(NIX + NIW <= 4 * MT, "one transfer per pair of products");
 
     f32x16 acc[MT][2];
 #pragma unroll
@@ -177,12 +181,14 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     const int ktiles_all = p.K / kBK;
     const int kt_begin = MODE == kPlainF32 ? (int)((int64_t)ktiles_all * piece / p.ksplit) : 0;
     const int kt_end = MODE == kPlainF32 ? (int)((int64_t)ktiles_all * (piece + 1) / p.ksplit) : ktiles_all;
-    issue(kt_begin, 0);
+#pragma unroll
+    for (int j = 0; j < NIX + NIW; j++) issue_piece(kt_begin, 0, j);
     for (int kt = kt_begin; kt < kt_end; kt++) {
         const int stage = (kt - kt_begin) & 1;
         wait_all_memory();
         __syncthreads();
-        if (kt + 1 < kt_end) issue(kt + 1, stage ^ 1);
+        // the step after this one; past the end the last step is fetched once more into the buffer nobody reads
+        const int kt_next = min(kt + 1, kt_end - 1);
         const uint8_t* sb = smem + stage * STAGE;
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
@@ -196,6 +202,11 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
 #pragma unroll
                 for (int nt = 0; nt < 2; nt++)
                     acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nt], acc[mt][nt], 0, 0, 0);
+                {
+                    const int slot = ks * MT + mt;
+                    if (2 * slot < NIX + NIW) issue_piece(kt_next, stage ^ 1, 2 * slot);
+                    if (2 * slot + 1 < NIX + NIW) issue_piece(kt_next, stage ^ 1, 2 * slot + 1);
+                }
             }
         }
     }
@@ -384,15 +395,18 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
             cols[i] = idxp ? idxp[pos] : pos;
         }
     };
-    auto issue = [&](int kt, int stage) {
-        const uint16_t* as = abase + (int64_t)kt * kBK * a_row_stride;
-#pragma unroll
-        for (int i = 0; i < NIA; i++) load_global_to_lds_16B(as, aoff_g[i], lds0 + stage * STAGE + i * 4096);
-#pragma unroll
-        for (int i = 0; i < NIW; i++)
+    // One of the NIA + NIW transfers of contraction step kt into buffer `stage` (issued one by one between the
+    // products of the step before, not in one burst); the w2 pieces use the columns that load_cols brought.
+    auto issue_piece = [&](int kt, int stage, int j) {
+        if (j < NIA) {
+            load_global_to_lds_16B(abase + (int64_t)kt * kBK * a_row_stride, aoff_g[j], lds0 + stage * STAGE + j * 4096);
+        } else {
+            const int i = j - NIA;
             load_global_to_lds_16B(w2b, (uint32_t)min(max(cols[i], 0), p.F - 1) * (uint32_t)(p.D * 2) + wchunk[i],
                                    lds0 + stage * STAGE + AT + i * 4096);
+        }
     };
+    static_assert(NIA + NIW <= 4 * MT, "one transfer per pair of products");
 
     f32x16 acc[MT][2];
 #pragma unroll
@@ -410,17 +424,16 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
 
     if (ktiles > 0) {
         load_cols(0);
-        issue(0, 0);
-        if (ktiles > 1) load_cols(1);
+#pragma unroll
+        for (int j = 0; j < NIA + NIW; j++) issue_piece(0, 0, j);
+        load_cols(min(1, ktiles - 1));
     }
     for (int kt = 0; kt < ktiles; kt++) {
         const int stage = kt & 1;
         wait_all_memory();
         __syncthreads();
-        if (kt + 1 < ktiles) {
-            issue(kt + 1, stage ^ 1);
-            if (kt + 2 < ktiles) load_cols(kt + 2);
-        }
+        // the step after this one; past the end the last step is fetched once more into the buffer nobody reads
+        const int kt_next = min(kt + 1, ktiles - 1);
         const uint8_t* sa = smem + stage * STAGE;
         const uint8_t* sw = sa + AT;
 #pragma unroll
@@ -454,9 +467,16 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
 #pragma unroll
                 for (int nt = 0; nt < 2; nt++)
                     acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nt], acc[mt][nt], 0, 0, 0);
+                {
+                    const int slot = ks * MT + mt;
+                    if (2 * slot < NIA + NIW) issue_piece(kt_next, stage ^ 1, 2 * slot);
+                    if (2 * slot + 1 < NIA + NIW) issue_piece(kt_next, stage ^ 1, 2 * slot + 1);
+                }
             }
         }
+        load_cols(min(kt + 2, ktiles - 1));   // for the transfers that the next step issues
     }
+    wait_all_memory();  // the last step's transfers into the unused buffer must have landed before LDS is reused
 
     // ---- epilogue: fp32 tile through LDS, one half of the token rows at a time ----
     // What is added to (the cached output, or the bias of the dense form) is requested for both halves before the
