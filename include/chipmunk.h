@@ -74,6 +74,23 @@ int32_t chipmunk_voxel_reorder(const void* src, void* dst, int32_t* perm, int32_
 int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R, int C, int64_t ld, int k,
                            int32_t* idx, int32_t* counts, int k_stride, void* stream);
 
+/* Bit-packed column masks and their conversion to index lists (App. B.4 "Bitpacked Sparsity Masks": a layer's
+ * pattern is cached as one bit per (chunk, column), an eighth of a byte mask; Table 3 "mask to indices conversion":
+ * one kernel turns it into the lists the delta kernels walk).  mask: [R, ld_words] uint32, ld_words >= ceil(C/32);
+ * bit (j % 32) of word j / 32 of row r is set when column j of row r is selected; bits at or beyond C are ignored
+ * on input and written as zero.
+ *   chipmunk_mask_to_indices: idx[r, 0:counts[r]] = the selected columns of row r in ascending order, counts[r] =
+ *     their number: rows may select different numbers of columns.  A row with more than k_stride selected
+ *     columns keeps the first k_stride and reports counts[r] = k_stride.  Entries at or beyond counts[r] are left
+ *     untouched.  idx: [R, k_stride] int32; counts: [R] int32.
+ *   chipmunk_indices_to_mask: the inverse; row r of mask receives exactly the columns idx[r, 0:counts[r]] that lie
+ *     in [0, C) (a column listed twice sets its bit once).  C <= 2^20.
+ * Both are exact.  One workgroup per row. */
+int32_t chipmunk_mask_to_indices(const uint32_t* mask, int64_t ld_words, int R, int C,
+                                 int32_t* idx, int32_t* counts, int k_stride, void* stream);
+int32_t chipmunk_indices_to_mask(const int32_t* idx, const int32_t* counts, int R, int C, int k_stride,
+                                 uint32_t* mask, int64_t ld_words, void* stream);
+
 /* Column-sparse delta attention (Sec. 3.3.1 "Sparse Delta Steps"; Alg. 3).
  * For chunk i of (b,h) with S = idx[b,h,i,0:counts[b,h,i]] and each row n of it:
  *   out[n] = base[n] + o_scale * softmax_{j in S}(softmax_scale * <q[n],k[j]>) v[j]

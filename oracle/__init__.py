@@ -9,6 +9,8 @@ from .chipmunk_oracle import (  # noqa: F401
     voxel_perm,
     reorder_rows,
     topk_cols,
+    mask_to_indices,
+    indices_to_mask,
     attn_dense,
     attn_sparse_delta,
     attn_row_stats,

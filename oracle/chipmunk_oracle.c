@@ -148,6 +148,45 @@ int oracle_topk_cols(const float* cur, const float* prev, int R, int C, int64_t 
 }
 
 /* ------------------------------------------------------------------------ */
+/* Bit-packed column masks (App. B.4 "Bitpacked Sparsity Masks") and the conversion
+ * between a mask and the index list of its row (Table 3 "mask to indices").
+ * mask is [R, ld_words] 32-bit words; bit (j % 32) of word j / 32 stands for column j.
+ *   mask -> indices: the set columns below C in ascending order, at most k_stride of
+ *   them; counts[r] = how many were written.
+ *   indices -> mask: every bit of the row's words is cleared, then the bit of every
+ *   listed column that lies in [0, C) is set. */
+int oracle_mask_to_indices(const uint32_t* mask, int64_t ld_words, int R, int C,
+                           int32_t* idx, int32_t* counts, int k_stride) {
+    if (R < 0 || C < 1 || k_stride < 0 || ld_words < (C + 31) / 32) return -2;
+    for (int r = 0; r < R; r++) {
+        int n = 0;
+        for (int j = 0; j < C; j++) {
+            uint32_t word = mask[(int64_t)r * ld_words + j / 32];
+            if ((word >> (j % 32)) & 1u) {
+                if (n < k_stride) idx[(int64_t)r * k_stride + n] = j;
+                n++;
+            }
+        }
+        counts[r] = n < k_stride ? n : k_stride;
+    }
+    return 0;
+}
+
+int oracle_indices_to_mask(const int32_t* idx, const int32_t* counts, int R, int C, int k_stride,
+                           uint32_t* mask, int64_t ld_words) {
+    if (R < 0 || C < 1 || k_stride < 0 || ld_words < (C + 31) / 32) return -2;
+    for (int r = 0; r < R; r++) {
+        for (int w = 0; w < (C + 31) / 32; w++) mask[(int64_t)r * ld_words + w] = 0u;
+        int n = counts[r] < k_stride ? counts[r] : k_stride;
+        for (int j = 0; j < n; j++) {
+            int32_t col = idx[(int64_t)r * k_stride + j];
+            if (col >= 0 && col < C) mask[(int64_t)r * ld_words + col / 32] |= 1u << (col % 32);
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Dense attention and exact column sums (Sec. 3.3.1 "Dense Steps").
  *   P = softmax(scale * Q K^T) row-wise,  O = P V,
  *   D[b,h,i,j] = sum over the rows q of chunk i of P[b,h,q,j].

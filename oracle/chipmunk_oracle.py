@@ -45,6 +45,8 @@ def _load():
             "oracle_voxel_perm": [_i32] * 8 + [_ptr, _ptr],
             "oracle_reorder_rows": [_ptr, _ptr, _ptr, _i32, _i32, _i32, _i32],
             "oracle_topk_cols": [_ptr, _ptr, _i32, _i32, _i64, _i32, _ptr, _ptr, _i32],
+            "oracle_mask_to_indices": [_ptr, _i64, _i32, _i32, _ptr, _ptr, _i32],
+            "oracle_indices_to_mask": [_ptr, _ptr, _i32, _i32, _i32, _ptr, _i64],
             "oracle_attn_dense": [_ptr] * 5 + [_i32] * 6 + [_f64],
             "oracle_attn_sparse_delta": [_ptr] * 7 + [_i32] * 7 + [_f64, _f64],
             "oracle_attn_row_stats": [_ptr] * 4 + [_i32] * 5 + [_f64],
@@ -115,6 +117,29 @@ def topk_cols(cur, prev, k, k_stride=None, idx_fill=-1):
     _check(_load().oracle_topk_cols(_p(cur), _p(prev), R, C, C, k, _p(idx), _p(counts), k_stride),
            "oracle_topk_cols")
     return idx, counts
+
+
+def mask_to_indices(mask, C, k_stride, idx_fill=-1):
+    """mask [R, ld_words] uint32 (bit-packed rows) -> (idx [R, k_stride] int32, counts [R] int32).  App. B.4, Table 3."""
+    _arr(mask, np.uint32, None, "mask")
+    R, ld_words = mask.shape
+    idx = np.full((R, k_stride), idx_fill, np.int32)
+    counts = np.zeros(R, np.int32)
+    _check(_load().oracle_mask_to_indices(_p(mask), ld_words, R, C, _p(idx), _p(counts), k_stride),
+           "oracle_mask_to_indices")
+    return idx, counts
+
+
+def indices_to_mask(idx, counts, C, ld_words=None, fill=0):
+    """idx [R, k_stride] int32, counts [R] int32 -> mask [R, ld_words] uint32 (bit-packed rows).  App. B.4."""
+    _arr(idx, np.int32, None, "idx")
+    R, k_stride = idx.shape
+    _arr(counts, np.int32, (R,), "counts")
+    ld_words = -(-C // 32) if ld_words is None else ld_words
+    mask = np.full((R, ld_words), fill, np.uint32)
+    _check(_load().oracle_indices_to_mask(_p(idx), _p(counts), R, C, k_stride, _p(mask), ld_words),
+           "oracle_indices_to_mask")
+    return mask
 
 
 def attn_dense(q, k, v, c, scale, want_colsum=False):

@@ -29,6 +29,8 @@ _SIGNATURES = {
     "chipmunk_voxel_reorder": ([_c_ptr] * 4 + [_c_int] * 11 + [_c_ptr], ctypes.c_int32),
     "chipmunk_topk_cols": ([_c_ptr, _c_ptr, _c_int, _c_int, _c_i64, _c_int, _c_ptr, _c_ptr, _c_int, _c_ptr],
                            ctypes.c_int32),
+    "chipmunk_mask_to_indices": ([_c_ptr, _c_i64, _c_int, _c_int, _c_ptr, _c_ptr, _c_int, _c_ptr], ctypes.c_int32),
+    "chipmunk_indices_to_mask": ([_c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_ptr, _c_i64, _c_ptr], ctypes.c_int32),
     "chipmunk_attn_sparse_delta": ([_c_ptr] * 7 + [_c_int] * 6 + [_c_f32, _c_f32, _c_ptr], ctypes.c_int32),
     "chipmunk_attn_block_sparse_delta": ([_c_ptr] * 7 + [_c_int] * 6 + [_c_f32, _c_f32, _c_ptr], ctypes.c_int32),
     "chipmunk_attn_dense_workspace_bytes": ([_c_int] * 3, _c_size),
@@ -138,6 +140,22 @@ def topk_cols(cur, prev, k, idx, counts):
                                      cur.stride(0), k, _ptr(idx, torch.int32, "idx"),
                                      _ptr(counts, torch.int32, "counts"), idx.shape[-1], _stream()),
            "chipmunk_topk_cols")
+
+
+def mask_to_indices(mask, C, idx, counts):
+    """mask: int32 [R, ld_words] bit-packed rows; idx: int32 [R, k_stride]; counts: int32 [R] (both written)."""
+    R, ld_words = mask.shape
+    _check(load().chipmunk_mask_to_indices(_ptr(mask, torch.int32, "mask"), ld_words, R, C,
+                                           _ptr(idx, torch.int32, "idx"), _ptr(counts, torch.int32, "counts"),
+                                           idx.shape[-1], _stream()), "chipmunk_mask_to_indices")
+
+
+def indices_to_mask(idx, counts, C, mask):
+    """idx: int32 [R, k_stride]; counts: int32 [R]; mask: int32 [R, ld_words] bit-packed rows (written)."""
+    R, ld_words = mask.shape
+    _check(load().chipmunk_indices_to_mask(_ptr(idx, torch.int32, "idx"), _ptr(counts, torch.int32, "counts"), R, C,
+                                           idx.shape[-1], _ptr(mask, torch.int32, "mask"), ld_words, _stream()),
+           "chipmunk_indices_to_mask")
 
 
 def attn_sparse_delta(q, k, v, idx, counts, base, out, c, softmax_scale, o_scale):

@@ -135,6 +135,76 @@ def test_topk_ties_and_structured_scores(cm, oracle):
     assert np.array_equal(idx.cpu().numpy(), ref_idx)
 
 
+# --------------------------------------------------------- bit-packed masks ---
+
+@pytest.mark.parametrize("R,C,k", [
+    (16, 1024, 256),          # Tiny attention rows
+    (5, 1000, 1000),          # every column, C not a multiple of 32
+    (7, 33, 5),
+    (3, 1, 1),
+    (24, 12288, 1229),        # FLUX MLP rows
+    (6, 115456, 8082),        # HunyuanVideo attention rows: 3608 words per row
+    (2, 1 << 20, 70000),      # the longest row indices_to_mask accepts
+])
+def test_mask_conversions_bit_exact(cm, oracle, R, C, k):
+    """App. B.4 / Table 3: index lists -> bit-packed masks -> index lists, both kernels against the oracle, with
+    different numbers of selected columns per row."""
+    idx, counts = si.uniform_indices(R, C, k, 3, DEV, k_stride=k + 2)
+    counts[0] = 0
+    counts[R // 2] = max(1, k // 3)
+    idx[:, k:] = -9                                                       # beyond the counts: never read
+    words = -(-C // 32)
+    ld = words + 1
+    mask = torch.full((R, ld), -1, dtype=torch.int32, device=DEV)
+    cm.indices_to_mask(idx, counts, C, mask)
+    ref_mask = oracle.indices_to_mask(idx.cpu().numpy(), counts.cpu().numpy(), C, ld_words=ld, fill=0xffffffff)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), ref_mask)   # padding word untouched on both sides
+    back = torch.full((R, k + 2), -7, dtype=torch.int32, device=DEV)
+    back_counts = torch.full((R,), -7, dtype=torch.int32, device=DEV)
+    cm.mask_to_indices(mask, C, back, back_counts)
+    ref_idx, ref_counts = oracle.mask_to_indices(ref_mask, C, k + 2, idx_fill=-7)
+    assert np.array_equal(back_counts.cpu().numpy(), ref_counts)
+    assert np.array_equal(back.cpu().numpy(), ref_idx)
+    assert np.array_equal(ref_counts, counts.cpu().numpy())               # the round trip returns the lists
+    # a destination shorter than a row's population keeps the first columns
+    short = torch.full((R, max(1, k // 2)), -7, dtype=torch.int32, device=DEV)
+    cm.mask_to_indices(mask, C, short, back_counts)
+    ref_idx, ref_counts = oracle.mask_to_indices(ref_mask, C, max(1, k // 2), idx_fill=-7)
+    assert np.array_equal(short.cpu().numpy(), ref_idx) and np.array_equal(back_counts.cpu().numpy(), ref_counts)
+
+
+def test_attention_from_bit_packed_masks_with_variable_counts(cm, oracle):
+    """The memory-lean path: the pattern is kept as bit-packed masks whose rows select different numbers of
+    columns; one conversion gives the lists and counts the delta kernel walks."""
+    B, H, N, E, c = 1, 2, 900, 128, 192
+    NB = -(-N // c)
+    q, kk, v = recipes.attn_inputs(B, H, N, E, 8, DEV)
+    g = si.generator(8, DEV)
+    keep = torch.rand((B * H * NB, 1), generator=g, device=DEV) * 0.4            # 0 .. 40 % of the columns, per chunk
+    dense = torch.rand((B * H * NB, N), generator=g, device=DEV) < keep
+    dense[3] = False                                                             # one chunk selects nothing
+    rows = torch.nonzero(dense)                                                  # the masks come from a list -> mask call
+    k_stride = int(dense.sum(1).max())
+    lists = torch.zeros((B * H * NB, k_stride), dtype=torch.int32, device=DEV)
+    cnts = dense.sum(1).to(torch.int32)
+    for r in range(B * H * NB):
+        lists[r, :int(cnts[r])] = rows[rows[:, 0] == r, 1].to(torch.int32)
+    mask = torch.zeros((B * H * NB, -(-N // 32)), dtype=torch.int32, device=DEV)
+    cm.indices_to_mask(lists, cnts, N, mask)
+    idx = torch.full((B * H * NB, k_stride), -1, dtype=torch.int32, device=DEV)
+    counts = torch.zeros((B * H * NB,), dtype=torch.int32, device=DEV)
+    cm.mask_to_indices(mask, N, idx, counts)
+    assert torch.equal(counts, cnts) and int(counts.min()) == 0 and int(counts.max()) > int(counts.float().mean()) + 20
+    base = recipes.attn_base((B, H, N, E), max(int(counts.float().mean()), 1), "delta", 8, DEV)
+    out = torch.empty_like(base)
+    scale = 1.0 / math.sqrt(E)
+    cm.attn_sparse_delta(q, kk, v, idx.view(B, H, NB, -1), counts.view(B, H, NB), base, out, c, scale, 1.0)
+    basen = si.np_f32(base).astype(np.float64)
+    ref = oracle.attn_sparse_delta(si.np_f32(q), si.np_f32(kk), si.np_f32(v), idx.cpu().numpy().reshape(B, H, NB, -1),
+                                   counts.cpu().numpy().reshape(B, H, NB), basen, c, scale, 1.0)
+    assert rel_err(si.np_f32(out), ref, ref - basen) <= REL_TOL
+
+
 # ---------------------------------------------------------------- attention ---
 
 def _attn_case(B, H, N, E, c, k, seed, ragged, order="ascending", base_mode="unit"):

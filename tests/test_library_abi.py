@@ -67,6 +67,15 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert fb(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 1 << 25, 0.1, 1.0, None) == -2      # kb_stride * 128 overflows
     assert fb(a, a, a, a, a, a, a, 1, 1, 128, 128, 192, 8, float("nan"), 1.0, None) == -2
     assert fb(a, a, a, P(0x1002), a, a, a, 1, 1, 128, 128, 192, 8, 0.1, 1.0, None) == -3    # int32 alignment
+    # bit-packed masks
+    mi, im = lib.chipmunk_mask_to_indices, lib.chipmunk_indices_to_mask
+    assert mi(None, 4, 1, 100, a, a, 8, None) == -1
+    assert mi(a, 3, 1, 100, a, a, 8, None) == -2             # ld_words < ceil(C / 32)
+    assert mi(a, 4, 1, 100, a, a, -1, None) == -2
+    assert mi(P(0x1002), 4, 1, 100, a, a, 8, None) == -3
+    assert im(a, a, 1, 100, 8, None, 4, None) == -1
+    assert im(a, a, 1, (1 << 20) + 1, 8, a, 1 << 16, None) == -2   # longer than the row kept in LDS
+    assert im(a, a, 0, 100, 8, a, 4, None) == -2
     # top-k
     t = lib.chipmunk_topk_cols
     assert t(None, None, 1, 8, 8, 2, a, a, 2, None) == -1

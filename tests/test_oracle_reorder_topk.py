@@ -189,3 +189,42 @@ def test_topk_rejects_bad_arguments(oracle):
         oracle.topk_cols(cur, None, 5)
     with pytest.raises(ValueError):
         oracle.topk_cols(cur, None, 3, k_stride=2)
+
+
+# ----------------------------------------------------------------- bit-packed masks ---
+
+@pytest.mark.parametrize("R,C", [(3, 1), (4, 31), (4, 32), (5, 33), (3, 1000), (2, 4608)])
+def test_mask_conversions_against_numpy(oracle, R, C):
+    """App. B.4 / Table 3: a bit-packed row and its index list, against numpy's packbits / nonzero."""
+    rng = np.random.default_rng(C)
+    dense = rng.random((R, C)) < 0.3
+    dense[0] = False                                        # an empty row
+    dense[-1] = True                                        # a full row
+    words = -(-C // 32)
+    padded = np.zeros((R, words * 32), bool)
+    padded[:, :C] = dense
+    packed = np.packbits(padded, axis=1, bitorder="little").view(np.uint32).reshape(R, words)
+    k_stride = C
+    idx, counts = oracle.mask_to_indices(np.ascontiguousarray(packed), C, k_stride)
+    for r in range(R):
+        want = np.nonzero(dense[r])[0]
+        assert counts[r] == len(want) and np.array_equal(idx[r, :counts[r]], want)
+        assert (idx[r, counts[r]:] == -1).all()             # the rest of the row is untouched
+    # the inverse, with rubbish in the padding bits of the destination and out-of-range / repeated entries in the list
+    idx2 = np.concatenate([idx, np.full((R, 3), -1, np.int32)], axis=1)
+    idx2[:, -3] = np.where(counts > 0, idx[:, 0], -5)       # a repeat of the first entry (or a negative column)
+    idx2[:, -2] = C + 7                                     # beyond the last column
+    idx2 = np.ascontiguousarray(np.roll(idx2, 3, axis=1))   # rubbish first: the list is unsorted now
+    back = oracle.indices_to_mask(idx2, (counts + 3).astype(np.int32), C, fill=0xffffffff)
+    assert np.array_equal(back, packed)
+    # a list shorter than the mask's population keeps the first k_stride columns
+    short, short_counts = oracle.mask_to_indices(np.ascontiguousarray(packed), C, max(1, C // 8))
+    for r in range(R):
+        want = np.nonzero(dense[r])[0][:max(1, C // 8)]
+        assert short_counts[r] == len(want) and np.array_equal(short[r, :short_counts[r]], want)
+
+
+def test_mask_ignores_bits_beyond_the_last_column(oracle):
+    packed = np.full((2, 2), 0xffffffff, np.uint32)
+    idx, counts = oracle.mask_to_indices(packed, 40, 64)
+    assert counts.tolist() == [40, 40] and np.array_equal(idx[0, :40], np.arange(40))
