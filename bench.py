@@ -447,6 +447,9 @@ def main():
     ap.add_argument("--index-structures", action="store_true",
                     help="also time the attention kernel alone on two other index structures of the same size: "
                          "columns drawn uniformly per chunk, and whole blocks of 128 consecutive columns")
+    ap.add_argument("--mlp-overlap", action="store_true",
+                    help="also time the MLP delta with the cache write-back inside the second GEMM's launch "
+                         "(chipmunk_mlp_sparse_delta_overlapped) beside the plain call")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step captured as one HIP graph (reported beside the eager numbers)")
     ap.add_argument("--ceilings", action="store_true",
@@ -583,6 +586,23 @@ def main():
             "ms": ms, "columns_kept": kept, "useful_tflops": fl_blocks / (ms * 1e-3) / 1e12}
         del blocks, iu2
         del kinds, iu, ib
+
+    if args.mlp_overlap:
+        # same indices, the two step inputs alternating so that the deltas are not zero; plain and overlapped in turn
+        ws2 = torch.empty(max(cm.mlp_overlapped_workspace_bytes(st["B"], st["N"], st["D"], st["F"], st["c"], max(st["k_m"], 1)), 16),
+                          dtype=torch.uint8, device=dev)
+        t = Timer()
+        for i in range(12):
+            x_in = st["x_expects"][i & 1]
+            for name, fn, w in (("plain", cm.mlp_sparse_delta, st["ws_mlp"]), ("overlapped", cm.mlp_sparse_delta_overlapped, ws2)):
+                a, b = t.span(name) if i >= 2 else Timer().span("warm")
+                a.record()
+                fn(x_in, st["w1"], st["b1"], st["w2"], st["idx_m"], st["cnt_m"], st["a_cache"], st["m_cache"], st["c"],
+                   st["act"], w)
+                b.record()
+        torch.cuda.synchronize()
+        extra["mlp_writeback_overlap"] = {"plain_ms": t.mean_ms("plain"), "overlapped_ms": t.mean_ms("overlapped")}
+        del ws2
 
     if not args.no_dense:
         st["dense_out"] = torch.empty_like(st["x"])

@@ -242,6 +242,20 @@ int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const u
                                   int B, int N, int D, int F, int c, int k_stride, int act,
                                   void* ws, size_t ws_bytes, void* stream);
 
+/* The same column-sparse delta MLP with the activation-cache write-back taken out of the first GEMM's epilogue and
+ * run inside the second GEMM's launch (App. B.3.3: the memory-bound scatter of the cache updates is overlapped
+ * with the compute-bound second GEMM on compute units that its last round of tiles leaves idle).  The first GEMM
+ * leaves the new activations in the workspace in the layout of the deltas; the second launch carries one extra
+ * workgroup per chunk, with the highest ids, that copies them into a_cache.  Same arguments, and bit for bit the
+ * same a_cache and o_cache as chipmunk_mlp_sparse_delta.  ws: chipmunk_mlp_overlapped_workspace_bytes() (twice
+ * that of chipmunk_mlp_sparse_delta). */
+size_t chipmunk_mlp_overlapped_workspace_bytes(int B, int N, int D, int F, int c, int k_stride);
+int32_t chipmunk_mlp_sparse_delta_overlapped(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                                             const uint16_t* w2, const int32_t* idx, const int32_t* counts,
+                                             uint16_t* a_cache, int64_t a_ld, uint16_t* o_cache,
+                                             int B, int N, int D, int F, int c, int k_stride, int act,
+                                             void* ws, size_t ws_bytes, void* stream);
+
 /* Dense MLP of a dense step (Sec. 3.3.2 "Dense steps"; Alg. 5):
  *   a = act(x w1^T + b1) -> a_cache[b,f,n] (bf16, neuron-major);  out = a w2 + b2.
  * out: [B,N,D] bf16; b2: [D] bf16 or NULL; a_cache: [B,F,a_ld] bf16, written

@@ -46,6 +46,9 @@ _SIGNATURES = {
     "chipmunk_mlp_workspace_bytes": ([_c_int] * 6, _c_size),
     "chipmunk_mlp_sparse_delta": ([_c_ptr] * 7 + [_c_i64, _c_ptr] + [_c_int] * 7 + [_c_ptr, _c_size, _c_ptr],
                                   ctypes.c_int32),
+    "chipmunk_mlp_overlapped_workspace_bytes": ([_c_int] * 6, _c_size),
+    "chipmunk_mlp_sparse_delta_overlapped": ([_c_ptr] * 7 + [_c_i64, _c_ptr] + [_c_int] * 7 + [_c_ptr, _c_size, _c_ptr],
+                                             ctypes.c_int32),
     "chipmunk_mlp_dense": ([_c_ptr] * 7 + [_c_i64] + [_c_int] * 6 + [_c_ptr], ctypes.c_int32),
     "chipmunk_status_string": ([ctypes.c_int32], ctypes.c_char_p),
 }
@@ -271,6 +274,24 @@ def mlp_sparse_delta(x, w1, b1, w2, idx, counts, a_cache, o_cache, c, act, ws):
                                             idx.shape[-1], int(act), _ptr(ws, torch.uint8, "ws"),
                                             0 if ws is None else ws.numel(), _stream()),
            "chipmunk_mlp_sparse_delta")
+
+
+def mlp_overlapped_workspace_bytes(B, N, D, F, c, k_stride):
+    return int(load().chipmunk_mlp_overlapped_workspace_bytes(B, N, D, F, c, k_stride))
+
+
+def mlp_sparse_delta_overlapped(x, w1, b1, w2, idx, counts, a_cache, o_cache, c, act, ws):
+    """mlp_sparse_delta with the cache write-back inside the second GEMM's launch (workspace twice as large)."""
+    B, N, D = x.shape
+    F = w1.shape[0]
+    bf = torch.bfloat16
+    _check(load().chipmunk_mlp_sparse_delta_overlapped(_ptr(x, bf, "x"), _ptr(w1, bf, "w1"), _ptr(b1, bf, "b1"),
+                                                       _ptr(w2, bf, "w2"), _ptr(idx, torch.int32, "idx"),
+                                                       _ptr(counts, torch.int32, "counts"), _ptr(a_cache, bf, "a_cache"),
+                                                       a_cache.shape[-1], _ptr(o_cache, bf, "o_cache"), B, N, D, F, c,
+                                                       idx.shape[-1], int(act), _ptr(ws, torch.uint8, "ws"),
+                                                       0 if ws is None else ws.numel(), _stream()),
+           "chipmunk_mlp_sparse_delta_overlapped")
 
 
 def mlp_dense(x, w1, b1, w2, b2, out, a_cache, c, act):

@@ -82,6 +82,8 @@ struct Gemm1Params {
     const int32_t* counts;   // [units] or null
     uint16_t* a_cache;       // [B, F, a_ld]
     uint16_t* delta_t;       // workspace [units, k_pad, BM]
+    uint16_t* act_t;         // null, or workspace [units, k_pad, BM]: the new activations go here (same layout as
+                             // delta_t) instead of into a_cache; the second GEMM's launch writes them back
     float* out_f32;          // kPlainF32: [B*N, F]
     int64_t a_ld;
     int N, NB, D, F, K, ldx; // K = contraction length (D, or 2D for the split-precision scores GEMM)
@@ -290,7 +292,9 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
         }
         u32x4 a8 = *reinterpret_cast<const u32x4*>(smem + nl * TS + ch * 16);
         uint16_t* arow = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + tok0;
-        if (nvalid == 8) {
+        if (MODE == kSparseDelta && p.act_t) {   // deferred write-back: one coalesced store, whole cell
+            *reinterpret_cast<u32x4*>(p.act_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = a8;
+        } else if (nvalid == 8) {
             *reinterpret_cast<u32x4*>(arow) = a8;
         } else {  // the cells past N in the last chunk stay as they are
             for (int e = 0; e < nvalid; e++) arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
@@ -320,6 +324,11 @@ struct Gemm2Params {
     int N, NB, D, F, k_stride, k_pad;
     int dense;
     int col_tiles, units;    // launch geometry (see xcd_tile_of_block)
+    // Deferred cache write-back (App. B.3.3): workgroups with id >= tile_blocks, one per unit, copy the new
+    // activations that the first GEMM left in act_t into a_cache while the tile workgroups of this launch compute.
+    const uint16_t* act_t;   // null: no write-back workgroups
+    uint16_t* a_cache;
+    int tile_blocks;
 };
 
 template <int BM>
@@ -346,6 +355,29 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
     const int wm = w >> 1, wn = w & 1;
     const int l16 = lane & 15, mb = (lane >> 4) & 1, h = lane >> 5;
 
+    if (p.act_t && (int)blockIdx.x >= p.tile_blocks) {
+        // A write-back workgroup.  They have the highest ids, so they start when the tile workgroups' last round
+        // leaves compute units free, and their memory traffic runs beside that round's products.
+        const int u = (int)blockIdx.x - p.tile_blocks;
+        const int ub = u / p.NB, urow0 = (u % p.NB) * BM;
+        const int ucount = max(min(p.counts[u], p.k_stride), 0);
+        constexpr int CPR = BM / 8;
+        for (int item = tid; item < ucount * CPR; item += 256) {
+            const int s = item / CPR, ch = item - s * CPR;
+            const int tok0 = urow0 + ch * 8;
+            const int nvalid = min(8, p.N - tok0);
+            if (nvalid <= 0) continue;
+            const int f = min(max(p.idx[(int64_t)u * p.k_stride + s], 0), p.F - 1);
+            const u32x4 a8 = *reinterpret_cast<const u32x4*>(p.act_t + ((int64_t)u * p.k_pad + s) * BM + ch * 8);
+            uint16_t* arow = p.a_cache + ((int64_t)ub * p.F + f) * p.a_ld + tok0;
+            if (nvalid == 8) {
+                *reinterpret_cast<u32x4*>(arow) = a8;
+            } else {  // the cells past N in the last chunk stay as they are
+                for (int e = 0; e < nvalid; e++) arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        return;
+    }
     int unit, col_tile;
     if (p.dense ? !xcd_tile_of_block_grouped(p.col_tiles, p.units, &unit, &col_tile)
                 : !xcd_tile_of_block(p.col_tiles, p.units, &unit, &col_tile))
@@ -618,7 +650,8 @@ static int32_t launch_gemm2(Gemm2Params p, int col_tiles, int units, hipStream_t
     if (hipFuncSetAttribute((const void*)mlp_gemm2_kernel<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
         hipSuccess)
         return CHIPMUNK_ERR_LAUNCH;
-    const int grid = p.dense ? xcd_grid_size_grouped(col_tiles, units) : xcd_grid_size(col_tiles, units);
+    p.tile_blocks = p.dense ? xcd_grid_size_grouped(col_tiles, units) : xcd_grid_size(col_tiles, units);
+    const int grid = p.tile_blocks + (p.act_t ? units : 0);
     hipLaunchKernelGGL((mlp_gemm2_kernel<BM>), dim3((unsigned)grid), dim3(256), lds, s, p);
     return launch_status();
 }
@@ -670,11 +703,12 @@ extern "C" size_t chipmunk_mlp_tile_mean_workspace_bytes(int B, int N, int D, in
     return tile_mean_bytes(B, N, D, F, c, tile_mean_pieces((int)units, F));
 }
 
-extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
-                                             const uint16_t* w2, const int32_t* idx, const int32_t* counts,
-                                             uint16_t* a_cache, int64_t a_ld, uint16_t* o_cache, int B, int N,
-                                             int D, int F, int c, int k_stride, int act, void* ws,
-                                             size_t ws_bytes, void* stream) {
+// The column-sparse delta MLP; `deferred`: the activation-cache write-back runs in the second GEMM's launch
+// (workspace: delta^T, then the new activations in the same layout).
+static int32_t run_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1, const uint16_t* w2,
+                                    const int32_t* idx, const int32_t* counts, uint16_t* a_cache, int64_t a_ld,
+                                    uint16_t* o_cache, int B, int N, int D, int F, int c, int k_stride, int act,
+                                    void* ws, size_t ws_bytes, void* stream, bool deferred) {
     if (!x || !w1 || !w2 || !idx || !counts || !a_cache || !o_cache) return CHIPMUNK_ERR_NULL;
     int32_t st = check_mlp_shapes(B, N, D, F, c);
     if (st != CHIPMUNK_OK) return st;
@@ -685,15 +719,17 @@ extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* 
         (a_ld % 8) != 0)
         return CHIPMUNK_ERR_ALIGN;
     if (k_stride == 0) return CHIPMUNK_OK;
-    size_t need = chipmunk_mlp_workspace_bytes(B, N, D, F, c, k_stride);
+    const size_t delta_bytes = chipmunk_mlp_workspace_bytes(B, N, D, F, c, k_stride);
+    const size_t need = deferred ? 2 * delta_bytes : delta_bytes;
     if (!ws || ws_bytes < need) return CHIPMUNK_ERR_WORKSPACE;
     const int NB = (N + c - 1) / c, units = B * NB;
     const int k_pad = round_up(k_stride, kBN);
     hipStream_t s = (hipStream_t)stream;
+    uint16_t* act_t = deferred ? (uint16_t*)((char*)ws + delta_bytes) : nullptr;
 
     Gemm1Params g1;
     g1.x = x; g1.w1 = w1; g1.b1 = b1; g1.idx = idx; g1.counts = counts; g1.a_cache = a_cache;
-    g1.delta_t = (uint16_t*)ws; g1.out_f32 = nullptr; g1.a_ld = a_ld;
+    g1.delta_t = (uint16_t*)ws; g1.act_t = act_t; g1.out_f32 = nullptr; g1.a_ld = a_ld;
     g1.N = N; g1.NB = NB; g1.D = D; g1.F = F; g1.K = D; g1.ldx = D;
     g1.k_stride = k_stride; g1.k_pad = k_pad; g1.act = act; g1.ksplit = 1;
     st = c == 192 ? launch_gemm1<192, kSparseDelta>(g1, k_pad / kBN, units, s)
@@ -703,7 +739,31 @@ extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* 
     Gemm2Params g2;
     g2.a_t = (const uint16_t*)ws; g2.w2 = w2; g2.bias = nullptr; g2.idx = idx; g2.counts = counts; g2.o = o_cache;
     g2.a_ld = a_ld; g2.N = N; g2.NB = NB; g2.D = D; g2.F = F; g2.k_stride = k_stride; g2.k_pad = k_pad; g2.dense = 0;
+    g2.act_t = act_t; g2.a_cache = a_cache;
     return c == 192 ? launch_gemm2<192>(g2, D / kBN, units, s) : launch_gemm2<128>(g2, D / kBN, units, s);
+}
+
+extern "C" int32_t chipmunk_mlp_sparse_delta(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                                             const uint16_t* w2, const int32_t* idx, const int32_t* counts,
+                                             uint16_t* a_cache, int64_t a_ld, uint16_t* o_cache, int B, int N,
+                                             int D, int F, int c, int k_stride, int act, void* ws,
+                                             size_t ws_bytes, void* stream) {
+    return run_mlp_sparse_delta(x, w1, b1, w2, idx, counts, a_cache, a_ld, o_cache, B, N, D, F, c, k_stride, act, ws,
+                                ws_bytes, stream, false);
+}
+
+extern "C" size_t chipmunk_mlp_overlapped_workspace_bytes(int B, int N, int D, int F, int c, int k_stride) {
+    return 2 * chipmunk_mlp_workspace_bytes(B, N, D, F, c, k_stride);
+}
+
+extern "C" int32_t chipmunk_mlp_sparse_delta_overlapped(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
+                                                        const uint16_t* w2, const int32_t* idx,
+                                                        const int32_t* counts, uint16_t* a_cache, int64_t a_ld,
+                                                        uint16_t* o_cache, int B, int N, int D, int F, int c,
+                                                        int k_stride, int act, void* ws, size_t ws_bytes,
+                                                        void* stream) {
+    return run_mlp_sparse_delta(x, w1, b1, w2, idx, counts, a_cache, a_ld, o_cache, B, N, D, F, c, k_stride, act, ws,
+                                ws_bytes, stream, true);
 }
 
 extern "C" int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, const uint16_t* b1,
@@ -723,7 +783,7 @@ extern "C" int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, con
 
     Gemm1Params g1;
     g1.x = x; g1.w1 = w1; g1.b1 = b1; g1.idx = nullptr; g1.counts = nullptr; g1.a_cache = a_cache;
-    g1.delta_t = nullptr; g1.out_f32 = nullptr; g1.a_ld = a_ld;
+    g1.delta_t = nullptr; g1.act_t = nullptr; g1.out_f32 = nullptr; g1.a_ld = a_ld;
     g1.N = N; g1.NB = NB; g1.D = D; g1.F = F; g1.K = D; g1.ldx = D;
     g1.k_stride = F; g1.k_pad = F; g1.act = act; g1.ksplit = 1;
     st = c == 192 ? launch_gemm1<192, kDenseAct>(g1, (F + kBN - 1) / kBN, units, s)
@@ -733,6 +793,7 @@ extern "C" int32_t chipmunk_mlp_dense(const uint16_t* x, const uint16_t* w1, con
     Gemm2Params g2;
     g2.a_t = a_cache; g2.w2 = w2; g2.bias = b2; g2.idx = nullptr; g2.counts = nullptr; g2.o = out;
     g2.a_ld = a_ld; g2.N = N; g2.NB = NB; g2.D = D; g2.F = F; g2.k_stride = F; g2.k_pad = F; g2.dense = 1;
+    g2.act_t = nullptr; g2.a_cache = nullptr;
     return c == 192 ? launch_gemm2<192>(g2, D / kBN, units, s) : launch_gemm2<128>(g2, D / kBN, units, s);
 }
 
@@ -748,7 +809,7 @@ static int32_t run_tile_mean(const uint16_t* x, const uint16_t* w1, float* T, in
     float* partial = pieces > 1 ? (float*)((char*)ws + means) : T;
     Gemm1Params g1;
     g1.x = (const uint16_t*)ws; g1.w1 = w1; g1.b1 = nullptr; g1.idx = nullptr; g1.counts = nullptr;
-    g1.a_cache = nullptr; g1.delta_t = nullptr; g1.out_f32 = partial; g1.a_ld = 0;
+    g1.a_cache = nullptr; g1.delta_t = nullptr; g1.act_t = nullptr; g1.out_f32 = partial; g1.a_ld = 0;
     g1.N = units; g1.NB = (units + 127) / 128; g1.D = D; g1.F = F; g1.K = 2 * D; g1.ldx = 2 * D;
     g1.k_stride = F; g1.k_pad = F; g1.act = 0; g1.ksplit = pieces;
     int32_t st = launch_gemm1<128, kPlainF32>(g1, (F + kBN - 1) / kBN, g1.NB, s);

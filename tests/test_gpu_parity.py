@@ -719,3 +719,59 @@ def test_mlp_full_shape_sampled_units(cm, oracle, name, chunks):
                                 np.ascontiguousarray(counts[:, i:i + 1].cpu().numpy()), a_u, o_u, c, act)
         assert rel_err(si.np_f32(a_cache[:, :, rows]), a_u) <= REL_TOL
         assert rel_err(si.np_f32(out[:, rows]), o_u, o_u - o_before) <= REL_TOL
+
+
+@pytest.mark.parametrize("B,N,D,F,c,k,act", [
+    (1, 1024, 256, 1024, 128, 256, 1),     # Tiny (config 0)
+    (2, 500, 256, 320, 192, 100, 0),       # ragged chunk, ragged counts
+    (1, 192, 128, 128, 192, 1, 1),
+])
+def test_mlp_overlapped_writeback_matches_plain(cm, oracle, B, N, D, F, c, k, act):
+    """App. B.3.3: the activation-cache write-back inside the second GEMM's launch.  Bit for bit the caches of the
+    plain entry point, over two chained steps, and within tolerance of the oracle."""
+    x1, x2, w1, b1, w2, b2 = recipes.mlp_inputs(B, N, D, F, 6, DEV)
+    a_ld = -(-N // 8) * 8 + 8
+    NB = -(-N // c)
+    o0 = torch.empty_like(x1)
+    a0 = torch.zeros((B, F, a_ld), dtype=torch.bfloat16, device=DEV)
+    cm.mlp_dense(x1, w1, b1, w2, b2, o0, a0, c, act)
+    plain = (a0.clone(), o0.clone())
+    over = (a0.clone(), o0.clone())
+    a_ref = si.np_f32(a0).astype(np.float64)
+    o_ref = si.np_f32(o0).astype(np.float64)
+    ws = _u8(cm.mlp_workspace_bytes(B, N, D, F, c, k))
+    ws2 = _u8(cm.mlp_overlapped_workspace_bytes(B, N, D, F, c, k))
+    assert ws2.numel() == 2 * ws.numel()
+    for step in range(2):
+        idx, counts = recipes.mlp_indices(B * NB, F, k, 20 + step, DEV, ragged=True)
+        idx, counts = idx.view(B, NB, k).contiguous(), counts.view(B, NB).contiguous()
+        cm.mlp_sparse_delta(x2, w1, b1, w2, idx, counts, plain[0], plain[1], c, act, ws)
+        cm.mlp_sparse_delta_overlapped(x2, w1, b1, w2, idx, counts, over[0], over[1], c, act, ws2)
+        assert torch.equal(over[0], plain[0]) and torch.equal(over[1], plain[1]), step
+        o_before = o_ref.copy()
+        oracle.mlp_sparse_delta(si.np_f32(x2), si.np_f32(w1), si.np_f32(b1), si.np_f32(w2), idx.cpu().numpy(),
+                                counts.cpu().numpy(), a_ref, o_ref, c, act)
+        assert rel_err(si.np_f32(over[0])[..., :N], a_ref[..., :N]) <= REL_TOL
+        assert rel_err(si.np_f32(over[1]), o_ref, o_ref - o_before) <= REL_TOL
+        assert torch.all(over[0][..., N:] == 0)                      # padding of the cache rows untouched
+        x2 = si.randn_bf16(tuple(x2.shape), si.generator(90 + step, DEV))
+
+
+def test_mlp_overlapped_writeback_hunyuan_shape(cm):
+    """The launch bench.py times: the same caches as the plain entry point at the full HunyuanVideo shape."""
+    cfg = si.CONFIGS["hunyuan"]
+    B, D, F, c = cfg["B"], cfg["D"], cfg["F"], cfg["c"]
+    N = si.config_tokens(cfg)
+    k = si.kept(F, cfg["mlp_keep"])
+    NB = -(-N // c)
+    x1, x2, w1, b1, w2, b2 = recipes.mlp_inputs(B, N, D, F, 7, DEV)
+    o0 = torch.empty_like(x1)
+    a0 = torch.zeros((B, F, N), dtype=torch.bfloat16, device=DEV)
+    cm.mlp_dense(x1, w1, b1, w2, b2, o0, a0, c, 1)
+    idx, counts = recipes.mlp_indices(B * NB, F, k, 7, DEV)
+    idx, counts = idx.view(B, NB, k).contiguous(), counts.view(B, NB).contiguous()
+    a1, o1 = a0.clone(), o0.clone()
+    cm.mlp_sparse_delta(x2, w1, b1, w2, idx, counts, a0, o0, c, 1, _u8(cm.mlp_workspace_bytes(B, N, D, F, c, k)))
+    cm.mlp_sparse_delta_overlapped(x2, w1, b1, w2, idx, counts, a1, o1, c, 1,
+                                   _u8(cm.mlp_overlapped_workspace_bytes(B, N, D, F, c, k)))
+    assert torch.equal(a1, a0) and torch.equal(o1, o0)

@@ -97,6 +97,10 @@ def test_bad_arguments_are_rejected_without_a_launch(lib):
     assert m(a, a, None, a, a, a, a, 100, a, 1, 128, 256, 1024, 128, 16, 1, a, 1 << 30, None) == -2  # a_ld < N
     assert m(a, a, None, a, a, a, a, 132, a, 1, 128, 256, 1024, 128, 16, 1, a, 1 << 30, None) == -3  # a_ld % 8
     assert m(a, a, None, a, a, a, a, 128, a, 1, 128, 256, 1024, 128, 16, 7, a, 1 << 30, None) == -4  # act
+    mo = lib.chipmunk_mlp_sparse_delta_overlapped
+    assert lib.chipmunk_mlp_overlapped_workspace_bytes(1, 1024, 256, 1024, 128, 256) == 2 * 8 * 256 * 128 * 2
+    assert mo(a, a, None, a, a, a, a, 128, a, 1, 128, 256, 1024, 128, 16, 1, a, 128 * 128 * 2, None) == -5   # one workspace is not enough
+    assert mo(a, a, None, a, None, a, a, 128, a, 1, 128, 256, 1024, 128, 16, 1, a, 1 << 30, None) == -1
     assert lib.chipmunk_mlp_workspace_bytes(1, 1024, 256, 1024, 128, 256) == 8 * 256 * 128 * 2
     assert lib.chipmunk_mlp_workspace_bytes(1, 1024, 256, 1024, 100, 256) == 0
     d = lib.chipmunk_attn_dense
