@@ -58,17 +58,23 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
     return v + add;
 }
 
-// exclusive prefix sum of one value per thread over the 256 threads of the
-// workgroup; *total receives the sum.  s_wave: 4 words of LDS.
+// exclusive prefix sum of one value per thread over the NT threads of the
+// workgroup; *total receives the sum.  s_wave: NT / 64 words of LDS.
+template <int NT>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave, uint32_t* total) {
     uint32_t inc = wave_inclusive_scan(v);
     int w = threadIdx.x >> 6;
     __syncthreads();  // s_wave may still be read by a previous call
     if ((threadIdx.x & 63) == 63) s_wave[w] = inc;
     __syncthreads();
-    uint32_t w0 = s_wave[0], w1 = s_wave[1], w2 = s_wave[2], w3 = s_wave[3];
-    uint32_t before = (w > 0 ? w0 : 0u) + (w > 1 ? w1 : 0u) + (w > 2 ? w2 : 0u);
-    *total = w0 + w1 + w2 + w3;
+    uint32_t before = 0, sum = 0;
+#pragma unroll
+    for (int i = 0; i < NT / 64; i++) {
+        const uint32_t wi = s_wave[i];
+        before += i < w ? wi : 0u;
+        sum += wi;
+    }
+    *total = sum;
     return before + inc - v;
 }
 
@@ -122,20 +128,20 @@ struct LdsKeys {
 
 // One radix digit: s_hist[d] = how many of the n keys behind `src` agree with `known`
 // on the bits selected by hi_mask and have digit d = (key >> shift) & digit_mask.
-template <typename Src>
+template <int NT, typename Src>
 __device__ __forceinline__ void digit_histogram(const Src& src, int n, uint32_t known, uint32_t hi_mask, int shift,
                                                 uint32_t digit_mask, uint32_t* s_hist) {
     const int tid = threadIdx.x;
     const int n4 = (n + 3) >> 2;
     __syncthreads();
-    for (int b = tid; b < kBins; b += 256) s_hist[b] = 0;
+    for (int b = tid; b < kBins; b += NT) s_hist[b] = 0;
     __syncthreads();
-    for (int j4 = tid; j4 < n4; j4 += 512) {
-        typename Src::Raw raw0 = src.load(j4), raw1 = src.load(j4 + 256);
+    for (int j4 = tid; j4 < n4; j4 += 2 * NT) {
+        typename Src::Raw raw0 = src.load(j4), raw1 = src.load(j4 + NT);
         uint32_t key[2][4];
         int valid[2];
         valid[0] = src.keys(raw0, j4, key[0]);
-        valid[1] = src.keys(raw1, j4 + 256, key[1]);
+        valid[1] = src.keys(raw1, j4 + NT, key[1]);
 #pragma unroll
         for (int h = 0; h < 2; h++)
 #pragma unroll
@@ -148,28 +154,28 @@ __device__ __forceinline__ void digit_histogram(const Src& src, int n, uint32_t 
 
 // For each of NQ ranks (1-based, counted from the highest digit down): the digit whose
 // bin holds that rank, and the rank inside the bin.  s_pick: 2 NQ words.
-template <int NQ>
+template <int NT, int NQ>
 __device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const uint32_t* s_hist, uint32_t* s_wave,
                                             uint32_t* s_pick, uint32_t (&digit)[NQ], uint32_t (&rest)[NQ]) {
     const int tid = threadIdx.x;
-    // thread t owns the 8 bins 2047-8t .. 2040-8t (descending)
-    uint32_t mine[8];
+    constexpr int PER = kBins / NT;   // thread t owns the bins 2047 - PER t .. (descending)
+    uint32_t mine[PER];
     uint32_t sum = 0;
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-        mine[e] = s_hist[kBins - 1 - (8 * tid + e)];
+    for (int e = 0; e < PER; e++) {
+        mine[e] = s_hist[kBins - 1 - (PER * tid + e)];
         sum += mine[e];
     }
     uint32_t total;
-    const uint32_t above = block_exclusive_scan(sum, s_wave, &total);
+    const uint32_t above = block_exclusive_scan<NT>(sum, s_wave, &total);
 #pragma unroll
     for (int q = 0; q < NQ; q++) {
         if (above < want[q] && want[q] <= above + sum) {
             uint32_t acc = above;
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
+            for (int e = 0; e < PER; e++) {
                 if (acc < want[q] && want[q] <= acc + mine[e]) {
-                    s_pick[2 * q] = (uint32_t)(kBins - 1 - (8 * tid + e));
+                    s_pick[2 * q] = (uint32_t)(kBins - 1 - (PER * tid + e));
                     s_pick[2 * q + 1] = want[q] - acc;
                 }
                 acc += mine[e];
@@ -189,8 +195,8 @@ __device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const ui
 // from bit low_bits down to bit stop_bits; the result is the selected key with the bits
 // below stop_bits cleared, and *take_eq receives the rank left inside the last bin (with
 // stop_bits = 0: how many keys equal to the result rank at or above it).
-// Called by all 256 threads; s_hist: kBins words, s_wave: 4 words, s_pick: 4 words.
-template <typename Src>
+// Called by all NT threads; s_hist: kBins words, s_wave: NT / 64 words, s_pick: 4 words.
+template <int NT, typename Src>
 __device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t rank, uint32_t* s_hist,
                                                  uint32_t* s_wave, uint32_t* s_pick, uint32_t* take_eq,
                                                  uint32_t known = 0, int low_bits = 32, int stop_bits = 0) {
@@ -201,9 +207,9 @@ __device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t
         const int width = min(11, remaining);
         const int shift = remaining - width;
         const uint32_t hi_mask = remaining >= 32 ? 0u : ~((1u << remaining) - 1u);
-        digit_histogram(src, n, known, hi_mask, shift, (1u << width) - 1u, s_hist);
+        digit_histogram<NT>(src, n, known, hi_mask, shift, (1u << width) - 1u, s_hist);
         uint32_t digit[1];
-        pick_digits<1>(want, s_hist, s_wave, s_pick, digit, want);
+        pick_digits<NT, 1>(want, s_hist, s_wave, s_pick, digit, want);
         known |= digit[0] << shift;
         remaining = shift;
     }
@@ -214,38 +220,38 @@ __device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t
 
 // The leading 22 bits of the rank_a-th and of the rank_b-th largest key (low 10 bits
 // cleared).  While both ranks fall into the same bin, one histogram serves both.
-template <typename Src>
+template <int NT, typename Src>
 __device__ __forceinline__ void radix_select_pair(const Src& src, int n, uint32_t rank_a, uint32_t rank_b,
                                                   uint32_t* s_hist, uint32_t* s_wave, uint32_t* s_pick,
                                                   uint32_t* key_a, uint32_t* key_b) {
     uint32_t want[2] = {rank_a, rank_b}, digit[2], unused;
-    digit_histogram(src, n, 0u, 0u, 21, 0x7ffu, s_hist);
-    pick_digits<2>(want, s_hist, s_wave, s_pick, digit, want);
+    digit_histogram<NT>(src, n, 0u, 0u, 21, 0x7ffu, s_hist);
+    pick_digits<NT, 2>(want, s_hist, s_wave, s_pick, digit, want);
     if (digit[0] == digit[1]) {
         const uint32_t known = digit[0] << 21;
-        digit_histogram(src, n, known, 0xffe00000u, 10, 0x7ffu, s_hist);
-        pick_digits<2>(want, s_hist, s_wave, s_pick, digit, want);
+        digit_histogram<NT>(src, n, known, 0xffe00000u, 10, 0x7ffu, s_hist);
+        pick_digits<NT, 2>(want, s_hist, s_wave, s_pick, digit, want);
         *key_a = known | (digit[0] << 10);
         *key_b = known | (digit[1] << 10);
         __syncthreads();
     } else {
-        *key_a = radix_select(src, n, want[0], s_hist, s_wave, s_pick, &unused, digit[0] << 21, 21, 10);
-        *key_b = radix_select(src, n, want[1], s_hist, s_wave, s_pick, &unused, digit[1] << 21, 21, 10);
+        *key_a = radix_select<NT>(src, n, want[0], s_hist, s_wave, s_pick, &unused, digit[0] << 21, 21, 10);
+        *key_b = radix_select<NT>(src, n, want[1], s_hist, s_wave, s_pick, &unused, digit[1] << 21, 21, 10);
     }
 }
 
 // Ordered emission: every column whose key exceeds thr, and the first take_eq
 // columns whose key equals it, in ascending column order.  One iteration covers
-// 4096 columns: wave w owns columns [1024 w, 1024 w + 1024) of them as four
+// 16 NT columns: wave w owns columns [1024 w, 1024 w + 1024) of them as four
 // coalesced groups of 256, so one cross-wave exchange serves 16 keys per thread.
-template <typename Src>
+template <int NT, typename Src>
 __device__ __forceinline__ void emit_selected(const Src& src, int C, uint32_t thr, uint32_t take_eq,
                                               int32_t* __restrict__ out, uint32_t* s_wave) {
     constexpr int U = 4;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int C4 = (C + 3) >> 2;
     uint32_t run_gt = 0, run_eq = 0;
-    for (int base4 = 0; base4 < C4; base4 += 256 * U) {
+    for (int base4 = 0; base4 < C4; base4 += NT * U) {
         uint32_t key[U][4];
         int valid[U], j4[U];
         typename Src::Raw raw[U];
@@ -275,9 +281,13 @@ __device__ __forceinline__ void emit_selected(const Src& src, int C, uint32_t th
         __syncthreads();  // s_wave may still be read by the previous iteration
         if (lane == 0) s_wave[w] = wave_sum;
         __syncthreads();
-        uint32_t w0 = s_wave[0], w1 = s_wave[1], w2 = s_wave[2], w3 = s_wave[3];
-        uint32_t before = (w > 0 ? w0 : 0u) + (w > 1 ? w1 : 0u) + (w > 2 ? w2 : 0u);
-        uint32_t total = w0 + w1 + w2 + w3;
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int i = 0; i < NT / 64; i++) {
+            const uint32_t wi = s_wave[i];
+            before += i < w ? wi : 0u;
+            total += wi;
+        }
 #pragma unroll
         for (int u = 0; u < U; u++) {
             uint32_t mine = before + inc[u] - cnt[u];
@@ -333,85 +343,106 @@ __global__ __launch_bounds__(256) void topk_short_rows_kernel(const float* __res
     }
     LdsKeys src{s_keys, C};
     uint32_t take_eq;
-    uint32_t thr = radix_select(src, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
-    emit_selected(src, C, thr, take_eq, idx + row * (int64_t)k_stride, s_wave);
+    uint32_t thr = radix_select<256>(src, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
+    emit_selected<256>(src, C, thr, take_eq, idx + row * (int64_t)k_stride, s_wave);
 }
 
-// The candidates of a long row whose key equals the threshold, keyed so that the lower column ranks higher.
-struct CandidateTieKeys {
-    const uint32_t* ckey;
-    const uint32_t* ccol;
+// The candidates of a long row are (key, column) pairs.  Their keys:
+struct CandidateKeys {
+    const uint2* pairs;
     int n;
-    uint32_t thr;
     struct Raw {
-        uint4 k, c;
+        uint4 a, b;   // pairs 4 j4, 4 j4 + 1 and 4 j4 + 2, 4 j4 + 3
     };
     __device__ __forceinline__ Raw load(int j4) const {
-        const int j = min(j4, ((n + 3) >> 2) - 1);
-        return Raw{*reinterpret_cast<const uint4*>(ckey + 4 * j), *reinterpret_cast<const uint4*>(ccol + 4 * j)};
+        const uint4* at = reinterpret_cast<const uint4*>(pairs + 4 * min(j4, ((n + 3) >> 2) - 1));
+        return Raw{at[0], at[1]};
     }
     __device__ __forceinline__ int keys(const Raw& r, int j4, uint32_t (&key)[4]) const {
-        key[0] = r.k.x == thr ? ~r.c.x : 0u;
-        key[1] = r.k.y == thr ? ~r.c.y : 0u;
-        key[2] = r.k.z == thr ? ~r.c.z : 0u;
-        key[3] = r.k.w == thr ? ~r.c.w : 0u;
+        key[0] = r.a.x; key[1] = r.a.z; key[2] = r.b.x; key[3] = r.b.z;
         return max(0, min(4, n - 4 * j4));
     }
 };
 
+// Those whose key equals the threshold, keyed so that the lower column ranks higher.
+struct CandidateTieKeys {
+    const uint2* pairs;
+    int n;
+    uint32_t thr;
+    typedef CandidateKeys::Raw Raw;
+    __device__ __forceinline__ Raw load(int j4) const { return CandidateKeys{pairs, n}.load(j4); }
+    __device__ __forceinline__ int keys(const Raw& r, int j4, uint32_t (&key)[4]) const {
+        key[0] = r.a.x == thr ? ~r.a.y : 0u;
+        key[1] = r.a.z == thr ? ~r.a.w : 0u;
+        key[2] = r.b.x == thr ? ~r.b.y : 0u;
+        key[3] = r.b.z == thr ? ~r.b.w : 0u;
+        return max(0, min(4, n - 4 * j4));
+    }
+};
+
+constexpr int kLongThreads = 512;              // threads of a workgroup of the long-row kernel
+constexpr int kLongWaves = kLongThreads / 64;
+
 // State of one wave during the single pass over a long row.
 struct LongRowPass {
-    float f_hi, f_lo;         // the pivots, as scores
-    uint32_t* s_mask;         // one bit per column: bit (col & 31) of word col >> 5
-    uint32_t* s_ckey;         // this wave's candidate scores (raw bits) ...
-    uint32_t* s_ccol;         // ... and their columns
+    float f_hi, f_lo;         // the pivots, as scores (never NaN; f_lo <= f_hi)
+    uint32_t* s_mask;         // one bit per column: bit (col & 31) of word col >> 5; zero before the pass
+    uint2* s_cand;            // this wave's candidates: (raw bits of the score, column)
     uint32_t seg_cap;         // slots in this wave's candidate segment
     uint32_t slot;            // candidates appended so far (the same in every lane)
-    uint32_t n_above;         // per lane: bits set in the mask words this lane wrote
+    uint32_t n_above;         // per lane: mask bits this lane has set
+    uint32_t bit[4];          // the lane's four bits inside its mask word: 1 << (4 (lane % 8) + e)
     int C, G;                 // columns; groups of 256 columns
 };
 
-// One group of 256 columns: lane l holds the scores of columns 256 g + 4 l .. + 3.
-// Lanes 8 j .. 8 j + 7 combine their four "above the upper pivot" bits into mask word
-// 8 g + j; scores between the pivots are appended to the wave's candidates.
+// Appends the scores of the lanes named by `who` (`mine`: this lane is one of them) to the wave's candidates.
+__device__ __forceinline__ void long_row_append(LongRowPass& st, uint64_t who, bool mine, float score, int col) {
+    uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(who >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)who, st.slot));
+    pos = min(pos, st.seg_cap - 1u);  // an overflow is detected from the count
+    if (mine) st.s_cand[pos] = uint2{__float_as_uint(score), (uint32_t)col};
+    st.slot += (uint32_t)__builtin_popcountll(who);
+}
+
+// One group of 256 columns: lane l holds the scores of columns 256 g + 4 l .. + 3.  Its four "above the upper
+// pivot" bits are OR-ed into mask word 8 g + l / 8 by an LDS atomic; scores between the pivots are appended to
+// the wave's candidates.  About one score in fifty is a candidate, so a lane rarely has more than one: the first
+// candidate of every lane goes out in one step, further ones (some lane of the wave has one in about one group
+// out of six) in a step per element.  The order of the candidates does not matter.
+// The pass is bound by the number of vector and of scalar instructions a wave issues per group (a compute unit
+// runs out of issue slots before it runs out of memory bandwidth), hence the care: "between the pivots" is one
+// comparison (the median of score and pivots is the score), so that its lane mask is used as it comes, and lane
+// masks are combined as scalars.
 template <bool MASKED>
 __device__ __forceinline__ void long_row_group(LongRowPass& st, const float (&s)[4], int g, int lane) {
-    uint32_t nib = 0;
-    uint64_t cand[4];
-    bool mine[4];
     const int col0 = (g * 64 + lane) * 4;
+    bool between[4];
+    uint64_t cand[4];
+    uint32_t word = 0;
 #pragma unroll
-    for (int e = 3; e >= 0; e--) {
+    for (int e = 0; e < 4; e++) {
         bool above = s[e] > st.f_hi;
-        bool between = s[e] >= st.f_lo && s[e] <= st.f_hi;
+        between[e] = __builtin_amdgcn_fmed3f(s[e], st.f_lo, st.f_hi) == s[e];   // f_lo <= s <= f_hi
         if (MASKED) {
             const bool exists = col0 + e < st.C;
             above = above && exists;
-            between = between && exists;
+            between[e] = between[e] && exists;
         }
-        nib = nib * 2u + (above ? 1u : 0u);
-        mine[e] = between;
-        cand[e] = __builtin_amdgcn_ballot_w64(between);
+        word |= above ? st.bit[e] : 0u;
+        cand[e] = __builtin_amdgcn_ballot_w64(between[e]);
     }
-    uint32_t word = nib << ((lane & 7) * 4);
-    word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x111, 0xf, 0xf, false);  // row_shr:1
-    word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x112, 0xf, 0xf, false);  // row_shr:2
-    word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)word, 0x114, 0xf, 0xf, false);  // row_shr:4
-    if ((lane & 7) == 7 && (!MASKED || g < st.G)) {
-        st.s_mask[g * 8 + (lane >> 3)] = word;
-        st.n_above += __popc(word);
-    }
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        if (cand[e] != 0) {
-            uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(cand[e] >> 32),
-                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)cand[e], st.slot));
-            pos = min(pos, st.seg_cap - 1u);  // an overflow is detected from the count
-            if (mine[e]) {
-                st.s_ckey[pos] = __float_as_uint(s[e]);
-                st.s_ccol[pos] = (uint32_t)(col0 + e);
-            }
-            st.slot += (uint32_t)__builtin_popcountll(cand[e]);
+    if (!MASKED || g < st.G) atomicOr(&st.s_mask[g * 8 + (lane >> 3)], word);
+    st.n_above += __popc(word);
+    const uint64_t upto1 = cand[0] | cand[1], upto2 = upto1 | cand[2], any = upto2 | cand[3];
+    if (any != 0) {
+        const float first = between[0] ? s[0] : between[1] ? s[1] : between[2] ? s[2] : s[3];
+        const int first_e = between[0] ? 0 : between[1] ? 1 : between[2] ? 2 : 3;
+        long_row_append(st, any, between[0] || between[1] || between[2] || between[3], first, col0 + first_e);
+        const uint64_t more1 = cand[1] & cand[0], more2 = cand[2] & upto1, more3 = cand[3] & upto2;
+        if ((more1 | more2 | more3) != 0) {
+            if (more1 != 0) long_row_append(st, more1, between[1] && between[0], s[1], col0 + 1);
+            if (more2 != 0) long_row_append(st, more2, between[2] && (between[0] || between[1]), s[2], col0 + 2);
+            if (more3 != 0)
+                long_row_append(st, more3, between[3] && (between[0] || between[1] || between[2]), s[3], col0 + 3);
         }
     }
 }
@@ -427,7 +458,7 @@ __host__ __device__ inline void pivot_ranks(int k, int C, int S, int* rank_hi, i
     *rank_lo = (int)ceilf(r + margin) + 1;
 }
 
-// Rows too long for LDS.  With BRACKET the row is read from HBM once:
+// Rows too long for LDS; eight waves per row.  With BRACKET the row is read from HBM once:
 //   1. S scores are sampled as segments of 16 consecutive columns; two pivots that bracket
 //      the threshold with 3.5 standard deviations of slack are selected from the sample;
 //   2. one pass over the row records, as a bit per column in LDS, which scores exceed
@@ -438,21 +469,26 @@ __host__ __device__ inline void pivot_ranks(int k, int C, int S, int* rank_hi, i
 // If the bracket misses the threshold or the candidates overflow, or without BRACKET
 // (rows whose mask would not fit LDS), the threshold is selected by three histogram
 // passes over the row in global memory and a fourth pass writes the indices.
-// Dynamic LDS: kBins + 16 words, and with BRACKET max(S, 8 seg_cap + 8 ceil(C / 256)) more.
+// A wave alone needs about 600 cycles per 256 columns of the pass (its instructions issue in order), far more
+// than the memory system does, so the row is spread over eight waves; LDS allows three rows per CU.
+// Dynamic LDS: kBins + 32 words, and with BRACKET max(S, 2 kLongWaves seg_cap + 8 ceil(C / 256)) more.
 template <bool BRACKET, bool HAS_PREV, int S>
-__global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __restrict__ cur,
-                                                             const float* __restrict__ prev, int C, int64_t ld,
-                                                             int k, int32_t* __restrict__ idx,
-                                                             int32_t* __restrict__ counts, int k_stride, int seg_cap) {
+__global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const float* __restrict__ cur,
+                                                                      const float* __restrict__ prev, int C, int64_t ld,
+                                                                      int k, int32_t* __restrict__ idx,
+                                                                      int32_t* __restrict__ counts, int k_stride,
+                                                                      int seg_cap) {
+    constexpr int NT = kLongThreads, NW = kLongWaves;
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     uint32_t* s_hist = smem;                // kBins
-    uint32_t* s_wave = smem + kBins;        // 4
-    uint32_t* s_pick = s_wave + 4;          // 4
-    uint32_t* s_seg = s_pick + 4;           // 4: candidates appended by each wave
-    uint32_t* s_above = s_seg + 4;          // 1: scores above the upper pivot
-    uint32_t* s_ckey = smem + kBins + 16;   // 4 seg_cap: candidate scores, later keys (the sample lies here first)
-    uint32_t* s_ccol = s_ckey + 4 * seg_cap;  // 4 seg_cap: candidate columns
-    uint32_t* s_mask = s_ccol + 4 * seg_cap;  // one bit per column
+    uint32_t* s_wave = smem + kBins;        // NW
+    uint32_t* s_pick = s_wave + NW;         // 4
+    uint32_t* s_seg = s_pick + 4;           // NW: candidates appended by each wave
+    uint32_t* s_above = s_seg + NW;         // 1: scores above the upper pivot
+    uint32_t* s_ckey = smem + kBins + 32;   // the sample's keys, then:
+    uint2* s_cand = reinterpret_cast<uint2*>(s_ckey);  // NW seg_cap candidates: (score, later key; column)
+    uint32_t* s_mask = s_ckey + 2 * NW * seg_cap;      // one bit per column
+    static_assert(2 * NW + 5 <= 32, "the small arrays fit their 32 words");
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row = blockIdx.x;
@@ -466,24 +502,18 @@ __global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __rest
     if constexpr (BRACKET) {
         // ---- 1. pivots from a sample ---------------------------------------------------------
         {
-            constexpr int kSegments = S / 16, kPerThread = kSegments / 256;
-            typename Row::Raw raw[kPerThread][4];
-            int start4[kPerThread];
+            constexpr int kSegments = S / 16;
+            static_assert(kSegments <= NT, "one segment per thread at most");
+            if (tid < kSegments) {
+                typename Row::Raw raw[4];
+                const int start4 = (int)(((int64_t)tid * C) / kSegments) >> 4 << 2;  // a multiple of 16 columns
 #pragma unroll
-            for (int j = 0; j < kPerThread; j++) {
-                const int segment = tid * kPerThread + j;
-                start4[j] = (int)(((int64_t)segment * C) / kSegments) >> 4 << 2;  // a multiple of 16 columns
-#pragma unroll
-                for (int v = 0; v < 4; v++) raw[j][v] = g.load(start4[j] + v);
-            }
-#pragma unroll
-            for (int j = 0; j < kPerThread; j++) {
+                for (int v = 0; v < 4; v++) raw[v] = g.load(start4 + v);
 #pragma unroll
                 for (int v = 0; v < 4; v++) {
                     uint32_t key[4];
-                    g.keys(raw[j][v], start4[j] + v, key);
-                    *reinterpret_cast<uint4*>(&s_ckey[16 * (tid * kPerThread + j) + 4 * v]) =
-                        uint4{key[0], key[1], key[2], key[3]};
+                    g.keys(raw[v], start4 + v, key);
+                    *reinterpret_cast<uint4*>(&s_ckey[16 * tid + 4 * v]) = uint4{key[0], key[1], key[2], key[3]};
                 }
             }
         }
@@ -495,28 +525,34 @@ __global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __rest
         uint32_t pivot_hi = 0xff800000u, pivot_lo = 0x007fffffu;  // keys of +infinity and -infinity
         // the pivots only have to bracket: 22 leading bits of the sample keys are enough
         if (rank_hi >= 1 && rank_lo <= S) {
-            radix_select_pair(sample, S, (uint32_t)rank_hi, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &pivot_hi,
-                              &pivot_lo);
+            radix_select_pair<NT>(sample, S, (uint32_t)rank_hi, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &pivot_hi,
+                                  &pivot_lo);
             pivot_hi |= 0x3ffu;
         } else if (rank_hi >= 1) {
-            pivot_hi = radix_select(sample, S, (uint32_t)rank_hi, s_hist, s_wave, s_pick, &unused, 0u, 32, 10) | 0x3ffu;
+            pivot_hi = radix_select<NT>(sample, S, (uint32_t)rank_hi, s_hist, s_wave, s_pick, &unused, 0u, 32, 10) | 0x3ffu;
         } else if (rank_lo <= S) {
-            pivot_lo = radix_select(sample, S, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &unused, 0u, 32, 10);
+            pivot_lo = radix_select<NT>(sample, S, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &unused, 0u, 32, 10);
         }
-        pivot_lo = max(pivot_lo, 1u);
+        // widened to the keys of -infinity and +infinity at most: as scores, neither pivot is a NaN
+        pivot_lo = max(pivot_lo, 0x007fffffu);
+        pivot_hi = min(pivot_hi, 0xff800000u);
         __syncthreads();  // the sample is dead from here on
+        const int G = (C4 + 63) >> 6;
+        for (int i = tid; i < 2 * G; i += NT) reinterpret_cast<uint4*>(s_mask)[i] = uint4{0u, 0u, 0u, 0u};
+        __syncthreads();  // the pass sets bits with atomics
 
         // ---- 2. one pass over the row ----------------------------------------------------------
-        // A batch is U groups of 256 columns; wave w takes batches w, w + 4, ...  The loads of the
+        // A batch is U groups of 256 columns; wave w takes batches w, w + NW, ...  The loads of the
         // next batch are issued before the current one is consumed.  Batches whose columns all
         // exist take the unmasked path; the one batch that holds the end of the row is masked.
-        constexpr int U = 8;
-        const int G = (C4 + 63) >> 6;
+        constexpr int U = HAS_PREV ? 2 : 4;
         const int full4 = C >> 2;                      // float4 groups that exist completely
         const int full_batches = full4 / (64 * U);
         const int last_safe4 = full4 - 64 * U;         // last start from which a whole batch is in bounds
-        LongRowPass st{score_of_key(pivot_hi), score_of_key(pivot_lo), s_mask, s_ckey + w * seg_cap,
-                       s_ccol + w * seg_cap, (uint32_t)seg_cap, 0u, 0u, C, G};
+        LongRowPass st{score_of_key(pivot_hi), score_of_key(pivot_lo), s_mask, s_cand + w * seg_cap,
+                       (uint32_t)seg_cap, 0u, 0u,
+                       {1u << (4 * (lane & 7)), 2u << (4 * (lane & 7)), 4u << (4 * (lane & 7)), 8u << (4 * (lane & 7))},
+                       C, G};
         const float4* cur4 = reinterpret_cast<const float4*>(g.cur);
         const float4* prev4 = reinterpret_cast<const float4*>(g.prev);
         float4 rc[U], rp[U];
@@ -529,7 +565,7 @@ __global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __rest
                 if constexpr (HAS_PREV) rp[u] = prev4[at + u * 64 + lane];
             }
         }
-        for (; b < full_batches; b += 4) {
+        for (; b < full_batches; b += NW) {
             float s[U][4];
 #pragma unroll
             for (int u = 0; u < U; u++) {
@@ -540,7 +576,7 @@ __global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __rest
                     s[u][0] = rc[u].x; s[u][1] = rc[u].y; s[u][2] = rc[u].z; s[u][3] = rc[u].w;
                 }
             }
-            const int at = min((b + 4) * 64 * U, last_safe4);
+            const int at = min((b + NW) * 64 * U, last_safe4);
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 rc[u] = cur4[at + u * 64 + lane];
@@ -564,62 +600,70 @@ __global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __rest
             }
         }
         if (lane == 0) s_seg[w] = st.slot;
-        if (st.n_above != 0) atomicAdd(s_above, st.n_above);
+        {
+            const uint32_t wave_above = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(st.n_above), 63);
+            if (lane == 0 && wave_above != 0) atomicAdd(s_above, wave_above);
+        }
         __syncthreads();
-        const uint32_t seg0 = s_seg[0], seg1 = s_seg[1], seg2 = s_seg[2], seg3 = s_seg[3];
+        uint32_t n_cand = 0, seg_max = 0;
+#pragma unroll
+        for (int i = 0; i < NW; i++) {
+            const uint32_t used = s_seg[i];
+            n_cand += used;
+            seg_max = max(seg_max, used);
+        }
         const uint32_t n_above = *s_above;
-        const uint32_t n_cand = seg0 + seg1 + seg2 + seg3;
-        const bool fits = max(max(seg0, seg1), max(seg2, seg3)) <= (uint32_t)seg_cap;
+        const bool fits = seg_max <= (uint32_t)seg_cap;
 
         if (fits && n_above < (uint32_t)k && (uint32_t)k <= n_above + n_cand) {
             // ---- 3. exact threshold among the candidates; set the bits of the selected ones --------
             // Scores become keys relative to the lower pivot, 1 .. span + 1, which need few digits;
             // the unused slots of every segment get key 0, below every candidate.
-            const int n_slots = 4 * seg_cap;
+            const int n_slots = NW * seg_cap;
             {
-                const uint32_t used = (uint32_t)__builtin_amdgcn_readfirstlane(
-                    (int)(w == 0 ? seg0 : w == 1 ? seg1 : w == 2 ? seg2 : seg3));
+                const uint32_t used = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_seg[w]);
                 for (uint32_t i = lane; i < (uint32_t)seg_cap; i += 64) {
-                    uint32_t* slot = st.s_ckey + i;
+                    uint32_t* slot = &st.s_cand[i].x;
                     *slot = i < used ? key_of_score(__uint_as_float(*slot)) - pivot_lo + 1u : 0u;
                 }
             }
             const int low_bits = 32 - __clz((int)(pivot_hi - pivot_lo + 1u));
             uint32_t take_eq;
-            LdsKeys cand{s_ckey, n_slots};
-            const uint32_t thr = radix_select(cand, n_slots, (uint32_t)k - n_above, s_hist, s_wave, s_pick, &take_eq, 0u,
-                                              low_bits);
+            CandidateKeys cand{s_cand, n_slots};
+            const uint32_t thr = radix_select<NT>(cand, n_slots, (uint32_t)k - n_above, s_hist, s_wave, s_pick, &take_eq,
+                                                  0u, low_bits);
             // candidates above the threshold are selected, and so are those equal to it unless there
             // are more of them than take_eq
             uint32_t n_eq = 0;
-            for (int i = tid; i < n_slots; i += 256) {
-                const uint32_t key = s_ckey[i], col = s_ccol[i];
-                if (key >= thr) atomicOr(&s_mask[col >> 5], 1u << (col & 31));
-                n_eq += key == thr;
+            for (int i = tid; i < n_slots; i += NT) {
+                const uint2 kc = s_cand[i];
+                if (kc.x >= thr) atomicOr(&s_mask[kc.y >> 5], 1u << (kc.y & 31));
+                n_eq += kc.x == thr;
             }
             uint32_t n_eq_total;
-            block_exclusive_scan(n_eq, s_wave, &n_eq_total);
+            block_exclusive_scan<NT>(n_eq, s_wave, &n_eq_total);
             if (n_eq_total != take_eq) {
                 // ties across the threshold: only the take_eq lowest columns among the equal ones stay
-                CandidateTieKeys ties{s_ckey, s_ccol, n_slots, thr};
-                const uint32_t tie_key = radix_select(ties, n_slots, take_eq, s_hist, s_wave, s_pick, &unused);
-                for (int i = tid; i < n_slots; i += 256) {
-                    const uint32_t key = s_ckey[i], col = s_ccol[i];
-                    if (key == thr && ~col < tie_key) atomicAnd(&s_mask[col >> 5], ~(1u << (col & 31)));
+                CandidateTieKeys ties{s_cand, n_slots, thr};
+                const uint32_t tie_key = radix_select<NT>(ties, n_slots, take_eq, s_hist, s_wave, s_pick, &unused);
+                for (int i = tid; i < n_slots; i += NT) {
+                    const uint2 kc = s_cand[i];
+                    if (kc.x == thr && ~kc.y < tie_key) atomicAnd(&s_mask[kc.y >> 5], ~(1u << (kc.y & 31)));
                 }
             }
             __syncthreads();
 
             // ---- 4. indices from the mask, ascending -----------------------------------------------
-            // Wave v owns a quarter of the mask words; per step its lanes take 64 consecutive words,
+            // Wave v owns one share of the mask words; per step its lanes take 64 consecutive words,
             // so neighbouring lanes write neighbouring output slots.
             const int n_words = 8 * G;
-            const int quarter = (n_words + 3) >> 2;
-            const int q_begin = min(n_words, w * quarter), q_end = min(n_words, q_begin + quarter);
+            const int share = (n_words + NW - 1) / NW;
+            const int q_begin = min(n_words, w * share), q_end = min(n_words, q_begin + share);
             uint32_t mine = 0;
             for (int wi = q_begin + lane; wi < q_end; wi += 64) mine += __popc(s_mask[wi]);
             uint32_t total;
-            const uint32_t wave_base = block_exclusive_scan(mine, s_wave, &total) - (wave_inclusive_scan(mine) - mine);
+            const uint32_t wave_base =
+                block_exclusive_scan<NT>(mine, s_wave, &total) - (wave_inclusive_scan(mine) - mine);
             uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_base);
             for (int w0 = q_begin; w0 < q_end; w0 += 64) {
                 const int wi = w0 + lane;
@@ -637,15 +681,16 @@ __global__ __launch_bounds__(256) void topk_long_rows_kernel(const float* __rest
         }
     }
     uint32_t take_eq;
-    const uint32_t thr = radix_select(g, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
-    emit_selected(g, C, thr, take_eq, out, s_wave);
+    const uint32_t thr = radix_select<NT>(g, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
+    emit_selected<NT>(g, C, thr, take_eq, out, s_wave);
 }
 
 constexpr size_t kMaxLdsBytes = 160 * 1024;
 
 // Launch shape of the single-pass kernel for rows of C columns of which k are kept: the
 // sample size and the candidate slots per wave (1.3 times the expected number plus slack,
-// as far as LDS allows).  Returns false when the column mask leaves no room for candidates.
+// as far as LDS allows, and no more than lets three rows share a CU's LDS when that is enough for the slack).
+// Returns false when the column mask leaves no room for candidates.
 struct LongRowPlan {
     int sample, seg_cap;
     size_t lds_bytes;
@@ -654,19 +699,23 @@ struct LongRowPlan {
 inline bool plan_long_rows(int C, int k, LongRowPlan* plan) {
     const int S = C >= 65536 ? 8192 : 4096;
     const size_t mask_words = 8 * (size_t)((C + 255) / 256);
-    const size_t fixed_words = kBins + 16;
-    if ((fixed_words + mask_words + 8 * 128) * 4 > kMaxLdsBytes) return false;
+    const size_t fixed_words = kBins + 32;
+    const size_t per_cap = 2 * kLongWaves;        // LDS words per slot of every wave's segment (score and column)
+    if ((fixed_words + mask_words + per_cap * 64) * 4 > kMaxLdsBytes) return false;
     int rank_hi, rank_lo;
     pivot_ranks(k, C, S, &rank_hi, &rank_lo);
     const double bracket = (double)(std::min(rank_lo, S + 1) - std::max(rank_hi, 0) + 1) / (double)S;
-    const size_t room = (kMaxLdsBytes / 4 - fixed_words - mask_words) / 8;
-    size_t seg_cap = (size_t)(bracket * (double)C * 1.3 / 4.0) + 96;
-    seg_cap = (std::min(std::min(seg_cap, room), (size_t)4096) + 63) / 64 * 64;
-    if (seg_cap > room) seg_cap -= 64;
+    const double expected = bracket * (double)C / kLongWaves;      // candidates per wave
+    const size_t room = (kMaxLdsBytes / 4 - fixed_words - mask_words) / per_cap;
+    const size_t room3 = kMaxLdsBytes / 4 / 3 > fixed_words + mask_words
+                             ? (kMaxLdsBytes / 4 / 3 - fixed_words - mask_words) / per_cap : 0;   // three rows per CU
+    size_t seg_cap = (size_t)(expected * 1.3) + 96;
+    if (seg_cap > room3 && (double)room3 >= expected * 1.15 + 64) seg_cap = room3;
+    seg_cap = std::min(std::min(seg_cap, room), (size_t)4096) / 16 * 16;
     plan->sample = S;
     plan->seg_cap = (int)seg_cap;
-    plan->lds_bytes = (fixed_words + std::max((size_t)S, 8 * seg_cap + mask_words)) * 4;
-    return true;
+    plan->lds_bytes = (fixed_words + std::max((size_t)S, per_cap * seg_cap + mask_words)) * 4;
+    return seg_cap >= 64;
 }
 
 }  // namespace chipmunk
@@ -681,7 +730,7 @@ extern "C" int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R
         (reinterpret_cast<uintptr_t>(counts) & 3u))
         return CHIPMUNK_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid((unsigned)R), block(256);
+    const dim3 grid((unsigned)R), block(256), block_long(kLongThreads);
     LongRowPlan plan;
     if (C <= kLdsCols) {
         auto kernel = prev ? topk_short_rows_kernel<true> : topk_short_rows_kernel<false>;
@@ -694,12 +743,12 @@ extern "C" int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)plan.lds_bytes) != hipSuccess)
             return CHIPMUNK_ERR_LAUNCH;
-        hipLaunchKernelGGL(kernel, grid, block, plan.lds_bytes, s, cur, prev, C, ld, k, idx, counts, k_stride,
+        hipLaunchKernelGGL(kernel, grid, block_long, plan.lds_bytes, s, cur, prev, C, ld, k, idx, counts, k_stride,
                            plan.seg_cap);
     } else {
         auto kernel = prev ? topk_long_rows_kernel<false, true, 4096> : topk_long_rows_kernel<false, false, 4096>;
-        hipLaunchKernelGGL(kernel, grid, block, (kBins + 16) * sizeof(uint32_t), s, cur, prev, C, ld, k, idx, counts,
-                           k_stride, 0);
+        hipLaunchKernelGGL(kernel, grid, block_long, (kBins + 32) * sizeof(uint32_t), s, cur, prev, C, ld, k, idx,
+                           counts, k_stride, 0);
     }
     return launch_status();
 }
