@@ -58,19 +58,31 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
     return v + add;
 }
 
+// The small shared arrays of the selection routines.
+struct SelectScratch {
+    uint32_t* hist;   // kBins words
+    uint32_t* wave;   // 2 (NT / 64) words: two sets of per-wave totals used in turn.  A set is written again only
+                      // after the barrier of the scan in between, which no thread passes before it has read
+                      // the set: one barrier per scan is enough
+    uint32_t* pick;   // 6 words
+    int flip;         // which set the next scan uses (the same in every thread)
+};
+
 // exclusive prefix sum of one value per thread over the NT threads of the
-// workgroup; *total receives the sum.  s_wave: NT / 64 words of LDS.
+// workgroup; *total receives the sum.
 template <int NT>
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave, uint32_t* total) {
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, SelectScratch& sc, uint32_t* total) {
+    constexpr int NW = NT / 64;
     uint32_t inc = wave_inclusive_scan(v);
     int w = threadIdx.x >> 6;
-    __syncthreads();  // s_wave may still be read by a previous call
-    if ((threadIdx.x & 63) == 63) s_wave[w] = inc;
+    uint32_t* set = sc.wave + sc.flip * NW;
+    sc.flip ^= 1;
+    if ((threadIdx.x & 63) == 63) set[w] = inc;
     __syncthreads();
     uint32_t before = 0, sum = 0;
 #pragma unroll
-    for (int i = 0; i < NT / 64; i++) {
-        const uint32_t wi = s_wave[i];
+    for (int i = 0; i < NW; i++) {
+        const uint32_t wi = set[i];
         before += i < w ? wi : 0u;
         sum += wi;
     }
@@ -126,15 +138,15 @@ struct LdsKeys {
     }
 };
 
-// One radix digit: s_hist[d] = how many of the n keys behind `src` agree with `known`
+// One radix digit: hist[d] = how many of the n keys behind `src` agree with `known`
 // on the bits selected by hi_mask and have digit d = (key >> shift) & digit_mask.
+// Nobody reads hist when this is called (every reader below ends with a barrier).
 template <int NT, typename Src>
 __device__ __forceinline__ void digit_histogram(const Src& src, int n, uint32_t known, uint32_t hi_mask, int shift,
-                                                uint32_t digit_mask, uint32_t* s_hist) {
+                                                uint32_t digit_mask, uint32_t* hist) {
     const int tid = threadIdx.x;
     const int n4 = (n + 3) >> 2;
-    __syncthreads();
-    for (int b = tid; b < kBins; b += NT) s_hist[b] = 0;
+    for (int b = tid; b < kBins; b += NT) hist[b] = 0;
     __syncthreads();
     for (int j4 = tid; j4 < n4; j4 += 2 * NT) {
         typename Src::Raw raw0 = src.load(j4), raw1 = src.load(j4 + NT);
@@ -147,27 +159,28 @@ __device__ __forceinline__ void digit_histogram(const Src& src, int n, uint32_t 
 #pragma unroll
             for (int e = 0; e < 4; e++)
                 if (e < valid[h] && (key[h][e] & hi_mask) == known)
-                    atomicAdd(&s_hist[(key[h][e] >> shift) & digit_mask], 1u);
+                    atomicAdd(&hist[(key[h][e] >> shift) & digit_mask], 1u);
     }
     __syncthreads();
 }
 
 // For each of NQ ranks (1-based, counted from the highest digit down): the digit whose
-// bin holds that rank, and the rank inside the bin.  s_pick: 2 NQ words.
+// bin holds that rank, the rank inside the bin, and how many keys the bin holds.
+// Ends with a barrier behind which nobody reads hist or sc.pick's previous contents any more.
 template <int NT, int NQ>
-__device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const uint32_t* s_hist, uint32_t* s_wave,
-                                            uint32_t* s_pick, uint32_t (&digit)[NQ], uint32_t (&rest)[NQ]) {
+__device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const uint32_t* hist, SelectScratch& sc,
+                                            uint32_t (&digit)[NQ], uint32_t (&rest)[NQ], uint32_t (&held)[NQ]) {
     const int tid = threadIdx.x;
     constexpr int PER = kBins / NT;   // thread t owns the bins 2047 - PER t .. (descending)
     uint32_t mine[PER];
     uint32_t sum = 0;
 #pragma unroll
     for (int e = 0; e < PER; e++) {
-        mine[e] = s_hist[kBins - 1 - (PER * tid + e)];
+        mine[e] = hist[kBins - 1 - (PER * tid + e)];
         sum += mine[e];
     }
     uint32_t total;
-    const uint32_t above = block_exclusive_scan<NT>(sum, s_wave, &total);
+    const uint32_t above = block_exclusive_scan<NT>(sum, sc, &total);
 #pragma unroll
     for (int q = 0; q < NQ; q++) {
         if (above < want[q] && want[q] <= above + sum) {
@@ -175,8 +188,9 @@ __device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const ui
 #pragma unroll
             for (int e = 0; e < PER; e++) {
                 if (acc < want[q] && want[q] <= acc + mine[e]) {
-                    s_pick[2 * q] = (uint32_t)(kBins - 1 - (PER * tid + e));
-                    s_pick[2 * q + 1] = want[q] - acc;
+                    sc.pick[3 * q] = (uint32_t)(kBins - 1 - (PER * tid + e));
+                    sc.pick[3 * q + 1] = want[q] - acc;
+                    sc.pick[3 * q + 2] = mine[e];
                 }
                 acc += mine[e];
             }
@@ -185,8 +199,9 @@ __device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const ui
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < NQ; q++) {
-        digit[q] = s_pick[2 * q];
-        rest[q] = s_pick[2 * q + 1];
+        digit[q] = sc.pick[3 * q];
+        rest[q] = sc.pick[3 * q + 1];
+        held[q] = sc.pick[3 * q + 2];
     }
 }
 
@@ -195,11 +210,11 @@ __device__ __forceinline__ void pick_digits(const uint32_t (&want)[NQ], const ui
 // from bit low_bits down to bit stop_bits; the result is the selected key with the bits
 // below stop_bits cleared, and *take_eq receives the rank left inside the last bin (with
 // stop_bits = 0: how many keys equal to the result rank at or above it).
-// Called by all NT threads; s_hist: kBins words, s_wave: NT / 64 words, s_pick: 4 words.
+// Called by all NT threads.
 template <int NT, typename Src>
-__device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t rank, uint32_t* s_hist,
-                                                 uint32_t* s_wave, uint32_t* s_pick, uint32_t* take_eq,
-                                                 uint32_t known = 0, int low_bits = 32, int stop_bits = 0) {
+__device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t rank, SelectScratch& sc,
+                                                 uint32_t* take_eq, uint32_t known = 0, int low_bits = 32,
+                                                 int stop_bits = 0) {
     uint32_t want[1] = {rank};
     int remaining = low_bits;
 #pragma unroll 1
@@ -207,37 +222,14 @@ __device__ __forceinline__ uint32_t radix_select(const Src& src, int n, uint32_t
         const int width = min(11, remaining);
         const int shift = remaining - width;
         const uint32_t hi_mask = remaining >= 32 ? 0u : ~((1u << remaining) - 1u);
-        digit_histogram<NT>(src, n, known, hi_mask, shift, (1u << width) - 1u, s_hist);
-        uint32_t digit[1];
-        pick_digits<NT, 1>(want, s_hist, s_wave, s_pick, digit, want);
+        digit_histogram<NT>(src, n, known, hi_mask, shift, (1u << width) - 1u, sc.hist);
+        uint32_t digit[1], held[1];
+        pick_digits<NT, 1>(want, sc.hist, sc, digit, want, held);
         known |= digit[0] << shift;
         remaining = shift;
     }
-    __syncthreads();
     *take_eq = want[0];
     return known;
-}
-
-// The leading 22 bits of the rank_a-th and of the rank_b-th largest key (low 10 bits
-// cleared).  While both ranks fall into the same bin, one histogram serves both.
-template <int NT, typename Src>
-__device__ __forceinline__ void radix_select_pair(const Src& src, int n, uint32_t rank_a, uint32_t rank_b,
-                                                  uint32_t* s_hist, uint32_t* s_wave, uint32_t* s_pick,
-                                                  uint32_t* key_a, uint32_t* key_b) {
-    uint32_t want[2] = {rank_a, rank_b}, digit[2], unused;
-    digit_histogram<NT>(src, n, 0u, 0u, 21, 0x7ffu, s_hist);
-    pick_digits<NT, 2>(want, s_hist, s_wave, s_pick, digit, want);
-    if (digit[0] == digit[1]) {
-        const uint32_t known = digit[0] << 21;
-        digit_histogram<NT>(src, n, known, 0xffe00000u, 10, 0x7ffu, s_hist);
-        pick_digits<NT, 2>(want, s_hist, s_wave, s_pick, digit, want);
-        *key_a = known | (digit[0] << 10);
-        *key_b = known | (digit[1] << 10);
-        __syncthreads();
-    } else {
-        *key_a = radix_select<NT>(src, n, want[0], s_hist, s_wave, s_pick, &unused, digit[0] << 21, 21, 10);
-        *key_b = radix_select<NT>(src, n, want[1], s_hist, s_wave, s_pick, &unused, digit[1] << 21, 21, 10);
-    }
 }
 
 // Ordered emission: every column whose key exceeds thr, and the first take_eq
@@ -246,7 +238,7 @@ __device__ __forceinline__ void radix_select_pair(const Src& src, int n, uint32_
 // coalesced groups of 256, so one cross-wave exchange serves 16 keys per thread.
 template <int NT, typename Src>
 __device__ __forceinline__ void emit_selected(const Src& src, int C, uint32_t thr, uint32_t take_eq,
-                                              int32_t* __restrict__ out, uint32_t* s_wave) {
+                                              int32_t* __restrict__ out, SelectScratch& sc) {
     constexpr int U = 4;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int C4 = (C + 3) >> 2;
@@ -278,13 +270,14 @@ __device__ __forceinline__ void emit_selected(const Src& src, int C, uint32_t th
             tot[u] = (uint32_t)__builtin_amdgcn_readlane((int)inc[u], 63);
             wave_sum += tot[u];
         }
-        __syncthreads();  // s_wave may still be read by the previous iteration
-        if (lane == 0) s_wave[w] = wave_sum;
+        uint32_t* set = sc.wave + sc.flip * (NT / 64);
+        sc.flip ^= 1;
+        if (lane == 0) set[w] = wave_sum;
         __syncthreads();
         uint32_t before = 0, total = 0;
 #pragma unroll
         for (int i = 0; i < NT / 64; i++) {
-            const uint32_t wi = s_wave[i];
+            const uint32_t wi = set[i];
             before += i < w ? wi : 0u;
             total += wi;
         }
@@ -316,12 +309,10 @@ __global__ __launch_bounds__(256) void topk_short_rows_kernel(const float* __res
                                                               int k, int32_t* __restrict__ idx,
                                                               int32_t* __restrict__ counts, int k_stride) {
     // dynamic LDS, sized to the row so that short rows leave room for more workgroups per CU:
-    // kBins + 8 words, then the row's keys (a multiple of four)
+    // kBins + 16 words, then the row's keys (a multiple of four)
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
-    uint32_t* s_hist = smem;
-    uint32_t* s_wave = smem + kBins;
-    uint32_t* s_pick = s_wave + 4;
-    uint32_t* s_keys = smem + kBins + 8;
+    SelectScratch sc{smem, smem + kBins, smem + kBins + 8, 0};
+    uint32_t* s_keys = smem + kBins + 16;
     const int tid = threadIdx.x;
     const int64_t row = blockIdx.x;
     if (tid == 0) counts[row] = k;
@@ -343,8 +334,8 @@ __global__ __launch_bounds__(256) void topk_short_rows_kernel(const float* __res
     }
     LdsKeys src{s_keys, C};
     uint32_t take_eq;
-    uint32_t thr = radix_select<256>(src, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
-    emit_selected<256>(src, C, thr, take_eq, idx + row * (int64_t)k_stride, s_wave);
+    uint32_t thr = radix_select<256>(src, C, (uint32_t)k, sc, &take_eq);
+    emit_selected<256>(src, C, thr, take_eq, idx + row * (int64_t)k_stride, sc);
 }
 
 // The candidates of a long row are (key, column) pairs.  Their keys:
@@ -382,6 +373,8 @@ struct CandidateTieKeys {
 
 constexpr int kLongThreads = 512;              // threads of a workgroup of the long-row kernel
 constexpr int kLongWaves = kLongThreads / 64;
+constexpr int kLongSmall = 48;                 // words of small shared arrays behind the histogram
+constexpr uint32_t kCrowdedBin = 16;           // sample keys in a pivot's bin beyond which the bin is resolved further
 
 // State of one wave during the single pass over a long row.
 struct LongRowPass {
@@ -471,7 +464,7 @@ __host__ __device__ inline void pivot_ranks(int k, int C, int S, int* rank_hi, i
 // passes over the row in global memory and a fourth pass writes the indices.
 // A wave alone needs about 600 cycles per 256 columns of the pass (its instructions issue in order), far more
 // than the memory system does, so the row is spread over eight waves; LDS allows three rows per CU.
-// Dynamic LDS: kBins + 32 words, and with BRACKET max(S, 2 kLongWaves seg_cap + 8 ceil(C / 256)) more.
+// Dynamic LDS: kBins + kLongSmall words, and with BRACKET 2 kLongWaves seg_cap + 8 ceil(C / 256) more.
 template <bool BRACKET, bool HAS_PREV, int S>
 __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const float* __restrict__ cur,
                                                                       const float* __restrict__ prev, int C, int64_t ld,
@@ -480,15 +473,14 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
                                                                       int seg_cap) {
     constexpr int NT = kLongThreads, NW = kLongWaves;
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
-    uint32_t* s_hist = smem;                // kBins
-    uint32_t* s_wave = smem + kBins;        // NW
-    uint32_t* s_pick = s_wave + NW;         // 4
-    uint32_t* s_seg = s_pick + 4;           // NW: candidates appended by each wave
+    SelectScratch sc{smem, smem + kBins, smem + kBins + 2 * NW, 0};   // hist, two sets of NW scan words, 6 pick words
+    uint32_t* s_seg = sc.pick + 6;          // NW: candidates appended by each wave
     uint32_t* s_above = s_seg + NW;         // 1: scores above the upper pivot
-    uint32_t* s_ckey = smem + kBins + 32;   // the sample's keys, then:
-    uint2* s_cand = reinterpret_cast<uint2*>(s_ckey);  // NW seg_cap candidates: (score, later key; column)
-    uint32_t* s_mask = s_ckey + 2 * NW * seg_cap;      // one bit per column
-    static_assert(2 * NW + 5 <= 32, "the small arrays fit their 32 words");
+    uint32_t* s_range = s_above + 1;        // 2 NW: every wave's smallest and largest sample key
+    static_assert(5 * NW + 7 <= kLongSmall, "the small arrays fit their words");
+    uint2* s_cand = reinterpret_cast<uint2*>(smem + kBins + kLongSmall);  // NW seg_cap candidates: (score, later key;
+                                                                          // column); a second histogram before that
+    uint32_t* s_mask = smem + kBins + kLongSmall + 2 * NW * seg_cap;      // one bit per column
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row = blockIdx.x;
@@ -501,50 +493,126 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
 
     if constexpr (BRACKET) {
         // ---- 1. pivots from a sample ---------------------------------------------------------
+        // Thread t < S / 16 holds segment t of the sample as 16 keys in registers; the sample never goes to LDS.
+        // While the loads are in flight: both histograms and the column mask are cleared.
+        constexpr int kSegments = S / 16;
+        static_assert(kSegments <= NT, "one segment per thread at most");
+        static_assert(2 * NW * 128 >= kBins, "the second histogram fits the smallest candidate area (seg_cap >= 128)");
+        const bool have = tid < kSegments;
+        const int G = (C4 + 63) >> 6;
+        uint32_t* hist2 = reinterpret_cast<uint32_t*>(s_cand);   // free until the pass
+        uint32_t skey[16];
         {
-            constexpr int kSegments = S / 16;
-            static_assert(kSegments <= NT, "one segment per thread at most");
-            if (tid < kSegments) {
-                typename Row::Raw raw[4];
-                const int start4 = (int)(((int64_t)tid * C) / kSegments) >> 4 << 2;  // a multiple of 16 columns
+            typename Row::Raw raw[4];
+            const int start4 = (int)(((int64_t)min(tid, kSegments - 1) * C) / kSegments) >> 4 << 2;  // 16 | column
 #pragma unroll
-                for (int v = 0; v < 4; v++) raw[v] = g.load(start4 + v);
+            for (int v = 0; v < 4; v++) raw[v] = g.load(start4 + v);
+            for (int i = tid; i < kBins / 4; i += NT) {
+                reinterpret_cast<uint4*>(sc.hist)[i] = uint4{0u, 0u, 0u, 0u};
+                reinterpret_cast<uint4*>(hist2)[i] = uint4{0u, 0u, 0u, 0u};
+            }
+            for (int i = tid; i < 2 * G; i += NT) reinterpret_cast<uint4*>(s_mask)[i] = uint4{0u, 0u, 0u, 0u};
+            if (tid == 0) *s_above = 0;
 #pragma unroll
-                for (int v = 0; v < 4; v++) {
-                    uint32_t key[4];
-                    g.keys(raw[v], start4 + v, key);
-                    *reinterpret_cast<uint4*>(&s_ckey[16 * tid + 4 * v]) = uint4{key[0], key[1], key[2], key[3]};
-                }
+            for (int v = 0; v < 4; v++) {
+                uint32_t key[4];
+                g.keys(raw[v], start4 + v, key);
+#pragma unroll
+                for (int e = 0; e < 4; e++) skey[4 * v + e] = key[e];
             }
         }
-        if (tid == 0) *s_above = 0;
+        // The sample's keys agree on their leading bits (scores of one row share sign and, mostly, exponent); the
+        // digits are taken below that common prefix, where the keys spread over the bins (digits of the leading
+        // bits would send a whole wave's atomics to a handful of bins).
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        if (have) {
+#pragma unroll
+            for (int j = 0; j < 16; j++) {
+                kmin = min(kmin, skey[j]);
+                kmax = max(kmax, skey[j]);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
+        }
+        if (lane == 0) {
+            s_range[w] = kmin;
+            s_range[NW + w] = kmax;
+        }
+        __syncthreads();   // also: histograms and mask are clear
+#pragma unroll
+        for (int i = 0; i < NW; i++) {
+            kmin = min(kmin, s_range[i]);
+            kmax = max(kmax, s_range[NW + i]);
+        }
+        int remaining = 32 - __clz((int)(kmin ^ kmax));          // bits in which the sample's keys can differ
+        if (kmin == kmax) remaining = 0;
+        const uint32_t prefix = remaining >= 32 ? 0u : (kmin >> remaining) << remaining;
+
         int rank_hi, rank_lo;
         pivot_ranks(k, C, S, &rank_hi, &rank_lo);
-        LdsKeys sample{s_ckey, S};
-        uint32_t unused;
-        uint32_t pivot_hi = 0xff800000u, pivot_lo = 0x007fffffu;  // keys of +infinity and -infinity
-        // the pivots only have to bracket: 22 leading bits of the sample keys are enough
-        if (rank_hi >= 1 && rank_lo <= S) {
-            radix_select_pair<NT>(sample, S, (uint32_t)rank_hi, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &pivot_hi,
-                                  &pivot_lo);
-            pivot_hi |= 0x3ffu;
-        } else if (rank_hi >= 1) {
-            pivot_hi = radix_select<NT>(sample, S, (uint32_t)rank_hi, s_hist, s_wave, s_pick, &unused, 0u, 32, 10) | 0x3ffu;
-        } else if (rank_lo <= S) {
-            pivot_lo = radix_select<NT>(sample, S, (uint32_t)rank_lo, s_hist, s_wave, s_pick, &unused, 0u, 32, 10);
+        // Both ranks are resolved (clamped into the sample); a pivot whose rank lies outside is replaced below.
+        uint32_t want[2] = {(uint32_t)max(rank_hi, 1), (uint32_t)min(rank_lo, S)}, digit[2], held[2];
+        uint32_t key_hi = prefix, key_lo = prefix;
+        int unresolved = remaining;                               // low bits of the pivots not resolved
+        auto sample_histogram = [&](uint32_t* hist, uint32_t known, int above_bit, int shift, uint32_t digit_mask) {
+            // keys that agree with `known` above bit `above_bit`
+            if (have) {
+#pragma unroll
+                for (int j = 0; j < 16; j++)
+                    if (above_bit >= 32 || (skey[j] >> above_bit) == (known >> above_bit))
+                        atomicAdd(&hist[(skey[j] >> shift) & digit_mask], 1u);
+            }
+            __syncthreads();
+        };
+        if (remaining > 0) {
+            const int width = min(11, remaining), shift = remaining - width;
+            sample_histogram(sc.hist, prefix, 32, shift, (1u << width) - 1u);
+            pick_digits<NT, 2>(want, sc.hist, sc, digit, want, held);
+            key_hi |= digit[0] << shift;
+            key_lo |= digit[1] << shift;
+            unresolved = shift;
+            // A bin that holds few sample keys is pivot enough (its upper or lower edge); a crowded one, as the
+            // bins of a heavy-tailed row are, is resolved by a second digit.
+            if (shift > 0 && (held[0] > kCrowdedBin || held[1] > kCrowdedBin)) {
+                const int width2 = min(11, shift), shift2 = shift - width2;
+                const uint32_t mask2 = (1u << width2) - 1u;
+                if (digit[0] == digit[1]) {
+                    sample_histogram(hist2, key_hi, shift, shift2, mask2);
+                    pick_digits<NT, 2>(want, hist2, sc, digit, want, held);
+                    key_hi |= digit[0] << shift2;
+                    key_lo |= digit[1] << shift2;
+                } else {
+                    // the first histogram is free again behind the barrier that ended pick_digits
+                    for (int i = tid; i < kBins / 4; i += NT) reinterpret_cast<uint4*>(sc.hist)[i] = uint4{0u, 0u, 0u, 0u};
+                    uint32_t one[1] = {want[0]}, d[1], h[1];
+                    sample_histogram(hist2, key_hi, shift, shift2, mask2);   // its barrier also covers the clearing
+                    pick_digits<NT, 1>(one, hist2, sc, d, one, h);
+                    key_hi |= d[0] << shift2;
+                    one[0] = want[1];
+                    sample_histogram(sc.hist, key_lo, shift, shift2, mask2);
+                    pick_digits<NT, 1>(one, sc.hist, sc, d, one, h);
+                    key_lo |= d[0] << shift2;
+                }
+                unresolved = shift2;
+            }
         }
+        uint32_t pivot_hi = key_hi | (unresolved >= 32 ? 0xffffffffu : (1u << unresolved) - 1u);
+        uint32_t pivot_lo = key_lo;
+        uint32_t unused;
         // widened to the keys of -infinity and +infinity at most: as scores, neither pivot is a NaN
+        if (rank_hi < 1) pivot_hi = 0xff800000u;
+        if (rank_lo > S) pivot_lo = 0x007fffffu;
         pivot_lo = max(pivot_lo, 0x007fffffu);
         pivot_hi = min(pivot_hi, 0xff800000u);
-        __syncthreads();  // the sample is dead from here on
-        const int G = (C4 + 63) >> 6;
-        for (int i = tid; i < 2 * G; i += NT) reinterpret_cast<uint4*>(s_mask)[i] = uint4{0u, 0u, 0u, 0u};
-        __syncthreads();  // the pass sets bits with atomics
 
         // ---- 2. one pass over the row ----------------------------------------------------------
         // A batch is U groups of 256 columns; wave w takes batches w, w + NW, ...  The loads of the
         // next batch are issued before the current one is consumed.  Batches whose columns all
         // exist take the unmasked path; the one batch that holds the end of the row is masked.
+        // (the second histogram, in the candidates' place, is dead: pick_digits ended with a barrier)
         constexpr int U = HAS_PREV ? 2 : 4;
         const int full4 = C >> 2;                      // float4 groups that exist completely
         const int full_batches = full4 / (64 * U);
@@ -630,8 +698,7 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
             const int low_bits = 32 - __clz((int)(pivot_hi - pivot_lo + 1u));
             uint32_t take_eq;
             CandidateKeys cand{s_cand, n_slots};
-            const uint32_t thr = radix_select<NT>(cand, n_slots, (uint32_t)k - n_above, s_hist, s_wave, s_pick, &take_eq,
-                                                  0u, low_bits);
+            const uint32_t thr = radix_select<NT>(cand, n_slots, (uint32_t)k - n_above, sc, &take_eq, 0u, low_bits);
             // candidates above the threshold are selected, and so are those equal to it unless there
             // are more of them than take_eq
             uint32_t n_eq = 0;
@@ -641,11 +708,11 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
                 n_eq += kc.x == thr;
             }
             uint32_t n_eq_total;
-            block_exclusive_scan<NT>(n_eq, s_wave, &n_eq_total);
+            block_exclusive_scan<NT>(n_eq, sc, &n_eq_total);
             if (n_eq_total != take_eq) {
                 // ties across the threshold: only the take_eq lowest columns among the equal ones stay
                 CandidateTieKeys ties{s_cand, n_slots, thr};
-                const uint32_t tie_key = radix_select<NT>(ties, n_slots, take_eq, s_hist, s_wave, s_pick, &unused);
+                const uint32_t tie_key = radix_select<NT>(ties, n_slots, take_eq, sc, &unused);
                 for (int i = tid; i < n_slots; i += NT) {
                     const uint2 kc = s_cand[i];
                     if (kc.x == thr && ~kc.y < tie_key) atomicAnd(&s_mask[kc.y >> 5], ~(1u << (kc.y & 31)));
@@ -663,7 +730,7 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
             for (int wi = q_begin + lane; wi < q_end; wi += 64) mine += __popc(s_mask[wi]);
             uint32_t total;
             const uint32_t wave_base =
-                block_exclusive_scan<NT>(mine, s_wave, &total) - (wave_inclusive_scan(mine) - mine);
+                block_exclusive_scan<NT>(mine, sc, &total) - (wave_inclusive_scan(mine) - mine);
             uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_base);
             for (int w0 = q_begin; w0 < q_end; w0 += 64) {
                 const int wi = w0 + lane;
@@ -681,8 +748,9 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
         }
     }
     uint32_t take_eq;
-    const uint32_t thr = radix_select<NT>(g, C, (uint32_t)k, s_hist, s_wave, s_pick, &take_eq);
-    emit_selected<NT>(g, C, thr, take_eq, out, s_wave);
+    __syncthreads();  // whatever the single-pass attempt left in flight in LDS is over
+    const uint32_t thr = radix_select<NT>(g, C, (uint32_t)k, sc, &take_eq);
+    emit_selected<NT>(g, C, thr, take_eq, out, sc);
 }
 
 constexpr size_t kMaxLdsBytes = 160 * 1024;
@@ -699,7 +767,7 @@ struct LongRowPlan {
 inline bool plan_long_rows(int C, int k, LongRowPlan* plan) {
     const int S = C >= 65536 ? 8192 : 4096;
     const size_t mask_words = 8 * (size_t)((C + 255) / 256);
-    const size_t fixed_words = kBins + 32;
+    const size_t fixed_words = kBins + kLongSmall;
     const size_t per_cap = 2 * kLongWaves;        // LDS words per slot of every wave's segment (score and column)
     if ((fixed_words + mask_words + per_cap * 64) * 4 > kMaxLdsBytes) return false;
     int rank_hi, rank_lo;
@@ -709,13 +777,13 @@ inline bool plan_long_rows(int C, int k, LongRowPlan* plan) {
     const size_t room = (kMaxLdsBytes / 4 - fixed_words - mask_words) / per_cap;
     const size_t room3 = kMaxLdsBytes / 4 / 3 > fixed_words + mask_words
                              ? (kMaxLdsBytes / 4 / 3 - fixed_words - mask_words) / per_cap : 0;   // three rows per CU
-    size_t seg_cap = (size_t)(expected * 1.3) + 96;
+    size_t seg_cap = std::max((size_t)(expected * 1.3) + 96, (size_t)128);
     if (seg_cap > room3 && (double)room3 >= expected * 1.15 + 64) seg_cap = room3;
     seg_cap = std::min(std::min(seg_cap, room), (size_t)4096) / 16 * 16;
     plan->sample = S;
     plan->seg_cap = (int)seg_cap;
-    plan->lds_bytes = (fixed_words + std::max((size_t)S, per_cap * seg_cap + mask_words)) * 4;
-    return seg_cap >= 64;
+    plan->lds_bytes = (fixed_words + per_cap * seg_cap + mask_words) * 4;
+    return seg_cap >= 128;   // the second histogram of the sample phase lies in the candidates' place
 }
 
 }  // namespace chipmunk
@@ -734,7 +802,7 @@ extern "C" int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R
     LongRowPlan plan;
     if (C <= kLdsCols) {
         auto kernel = prev ? topk_short_rows_kernel<true> : topk_short_rows_kernel<false>;
-        const size_t lds = (kBins + 8 + (size_t)((C + 3) / 4) * 4) * sizeof(uint32_t);
+        const size_t lds = (kBins + 16 + (size_t)((C + 3) / 4) * 4) * sizeof(uint32_t);
         hipLaunchKernelGGL(kernel, grid, block, lds, s, cur, prev, C, ld, k, idx, counts, k_stride);
     } else if (plan_long_rows(C, k, &plan)) {
         auto kernel = plan.sample == 8192
@@ -747,7 +815,7 @@ extern "C" int32_t chipmunk_topk_cols(const float* cur, const float* prev, int R
                            plan.seg_cap);
     } else {
         auto kernel = prev ? topk_long_rows_kernel<false, true, 4096> : topk_long_rows_kernel<false, false, 4096>;
-        hipLaunchKernelGGL(kernel, grid, block_long, (kBins + 32) * sizeof(uint32_t), s, cur, prev, C, ld, k, idx,
+        hipLaunchKernelGGL(kernel, grid, block_long, (kBins + kLongSmall) * sizeof(uint32_t), s, cur, prev, C, ld, k, idx,
                            counts, k_stride, 0);
     }
     return launch_status();
