@@ -91,8 +91,9 @@ __device__ __forceinline__ short4v lds_read_tr16_at(uint32_t addr) {
 // between(j), j = 0 .. E/16 - 1, is called after the j-th group of NQB products: the kernel issues one of the next
 // step's tile transfers there, so that the transfers are spread over the products instead of queueing up in one
 // burst during which the wave issues nothing else.
-// K operands are requested KPF groups ahead of the products that consume them (2; the kernel with the column sums
-// of Alg. 4 has no registers to spare and keeps 1)
+// K operands are requested KPF groups ahead of the products that consume them.  One group ahead is enough: the
+// other wave of the SIMD covers what latency is left, and deeper prefetch only costs registers (measured equal
+// for the column-sparse launch, 2 % slower for the dense one)
 template <int E, int NQB, int KPF, typename Between>
 __device__ __forceinline__ void attn_scores(f32x4 (&S)[2][NQB], const AttnState<E, NQB>& st, const uint32_t (&kaddr)[E / 32],
                                             int tile_off, Between&& between) {
@@ -185,7 +186,7 @@ __device__ __forceinline__ void attn_update_max(AttnState<E, NQB>& st, f32x4 (&S
 // The transposing V reads do not depend on the probabilities: the first kVPrefetch
 // operands are requested before the exponentials, the rest kVPrefetch steps ahead
 // of the MFMAs that consume them, so LDS latency stays off the MFMA chain.
-constexpr int kVPrefetch = 3;        // (2 in the kernel with the column sums)
+constexpr int kVPrefetch = 2;        // (1 in the kernel with the column sums)
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x) {  // x of the lane that the DPP control CTRL names
@@ -524,11 +525,11 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             const int tile_off = (half * kTilesPerStep + s) * STAGE;   // a constant once the loop over s is unrolled
             f32x4 S[2][NQB];
             if (s == 0) {
-                attn_scores<E, NQB, FUSED ? 1 : 2>(S, st, kaddr, tile_off,
+                attn_scores<E, NQB, 1>(S, st, kaddr, tile_off,
                                     [&](int j) { gather_piece(std::integral_constant<int, half ^ 1>{}, j); });
                 load_cols();
             } else {
-                attn_scores<E, NQB, FUSED ? 1 : 2>(S, st, kaddr, tile_off, [](int) {});
+                attn_scores<E, NQB, 1>(S, st, kaddr, tile_off, [](int) {});
             }
             if constexpr (BLOCKS) {   // only the sequence's last block can reach beyond N; it may stand anywhere in the list
                 const int col0 = block_now + (t * kTileRows) % kBlockColumns;
