@@ -732,17 +732,38 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
             const uint32_t wave_base =
                 block_exclusive_scan<NT>(mine, sc, &total) - (wave_inclusive_scan(mine) - mine);
             uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_base);
+            // The indices of a step go through LDS (the wave's candidate segment, dead by now), so that they leave
+            // as runs of 64 consecutive words per store instead of one scattered word per lane and set bit.
+            uint32_t* stage = reinterpret_cast<uint32_t*>(s_cand + w * seg_cap);
+            const uint32_t stage_cap = 2u * (uint32_t)seg_cap;
             for (int w0 = q_begin; w0 < q_end; w0 += 64) {
                 const int wi = w0 + lane;
                 uint32_t m = wi < q_end ? s_mask[wi] : 0u;
                 const uint32_t inc = wave_inclusive_scan(__popc(m));
-                uint32_t pos = base + inc - __popc(m);
-                base += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
-                while (m) {
-                    if (pos < (uint32_t)k) out[pos] = wi * 32 + __ffs((int)m) - 1;
-                    pos++;
-                    m &= m - 1;
+                const uint32_t step_total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+                uint32_t pos = inc - __popc(m);
+                if (step_total <= stage_cap) {
+                    while (m) {
+                        stage[pos++] = wi * 32 + __ffs((int)m) - 1;
+                        m &= m - 1;
+                    }
+                    // the wave's LDS accesses complete in order; only the compiler has to keep these apart
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    for (uint32_t i = lane; i < step_total; i += 64)
+                        if (base + i < (uint32_t)k) out[base + i] = (int32_t)stage[i];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                } else {   // a step that selects more than the segment holds: straight to memory
+                    pos += base;
+                    while (m) {
+                        if (pos < (uint32_t)k) out[pos] = wi * 32 + __ffs((int)m) - 1;
+                        pos++;
+                        m &= m - 1;
+                    }
                 }
+                base += step_total;
             }
             return;
         }
