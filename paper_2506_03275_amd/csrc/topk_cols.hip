@@ -501,12 +501,29 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
         const bool have = tid < kSegments;
         const int G = (C4 + 63) >> 6;
         uint32_t* hist2 = reinterpret_cast<uint32_t*>(s_cand);   // free until the pass
+        // the pass's batches (step 2): U groups of 256 columns each
+        constexpr int U = HAS_PREV ? 2 : 4;
+        const int full4 = C >> 2;                      // float4 groups that exist completely
+        const int full_batches = full4 / (64 * U);
+        const int last_safe4 = full4 - 64 * U;         // last start from which a whole batch is in bounds
+        const float4* cur4 = reinterpret_cast<const float4*>(g.cur);
+        const float4* prev4 = reinterpret_cast<const float4*>(g.prev);
+        float4 rc[U], rp[U];
+        int b = w;
         uint32_t skey[16];
         {
             typename Row::Raw raw[4];
             const int start4 = (int)(((int64_t)min(tid, kSegments - 1) * C) / kSegments) >> 4 << 2;  // 16 | column
 #pragma unroll
             for (int v = 0; v < 4; v++) raw[v] = g.load(start4 + v);
+            {   // the wave's first batch of the pass is requested behind the sample: it lands while the pivots are found
+                const int at = min(b * 64 * U, last_safe4);
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    rc[u] = cur4[at + u * 64 + lane];
+                    if constexpr (HAS_PREV) rp[u] = prev4[at + u * 64 + lane];
+                }
+            }
             for (int i = tid; i < kBins / 4; i += NT) {
                 reinterpret_cast<uint4*>(sc.hist)[i] = uint4{0u, 0u, 0u, 0u};
                 reinterpret_cast<uint4*>(hist2)[i] = uint4{0u, 0u, 0u, 0u};
@@ -613,26 +630,10 @@ __global__ __launch_bounds__(kLongThreads, 6) void topk_long_rows_kernel(const f
         // next batch are issued before the current one is consumed.  Batches whose columns all
         // exist take the unmasked path; the one batch that holds the end of the row is masked.
         // (the second histogram, in the candidates' place, is dead: pick_digits ended with a barrier)
-        constexpr int U = HAS_PREV ? 2 : 4;
-        const int full4 = C >> 2;                      // float4 groups that exist completely
-        const int full_batches = full4 / (64 * U);
-        const int last_safe4 = full4 - 64 * U;         // last start from which a whole batch is in bounds
         LongRowPass st{score_of_key(pivot_hi), score_of_key(pivot_lo), s_mask, s_cand + w * seg_cap,
                        (uint32_t)seg_cap, 0u, 0u,
                        {1u << (4 * (lane & 7)), 2u << (4 * (lane & 7)), 4u << (4 * (lane & 7)), 8u << (4 * (lane & 7))},
                        C, G};
-        const float4* cur4 = reinterpret_cast<const float4*>(g.cur);
-        const float4* prev4 = reinterpret_cast<const float4*>(g.prev);
-        float4 rc[U], rp[U];
-        int b = w;
-        {
-            const int at = min(b * 64 * U, last_safe4);
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                rc[u] = cur4[at + u * 64 + lane];
-                if constexpr (HAS_PREV) rp[u] = prev4[at + u * 64 + lane];
-            }
-        }
         for (; b < full_batches; b += NW) {
             float s[U][4];
 #pragma unroll
