@@ -117,6 +117,15 @@ __device__ __forceinline__ float rows4_sum(float x) {
 
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
+// Waits until at most N of the wave's vector memory loads (the asynchronous LDS transfers among them) are still
+// outstanding; they complete in the order they were issued.  (s_waitcnt: the count is split over bits 3:0 and
+// 15:14; the export and LDS/scalar counters are left at their maxima.)
+template <int N>
+__device__ __forceinline__ void wait_vmem_at_most() {
+    static_assert(N >= 0 && N < 64, "the counter has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | 0x0070 | 0x0f00);
+}
+
 // Workgroup barrier for data exchanged through LDS: waits for this wave's LDS accesses only, so that loads from
 // global memory into registers stay in flight across it (__syncthreads() waits for those as well).
 __device__ __forceinline__ void lds_accesses_then_barrier() {
