@@ -4,7 +4,8 @@
 //
 // GEMM1  pre[tok, s] = <x[tok], w1[idx[s]]>: one workgroup owns (token chunk,
 //        128 selected neurons).  The x tile and the gathered w1 rows stream
-//        through LDS (asynchronous 16-byte loads, double buffered, K tile 64)
+//        through LDS (asynchronous 16-byte loads, three tile buffers: two
+//        contraction steps in flight while one is consumed, K tile 64)
 //        into bf16 MFMA 32x32x16.  Epilogue: bias, activation, rounding to
 //        bf16, a transpose through LDS to the neuron-major layout of a_cache,
 //        then per 8 consecutive tokens of one neuron: read the cached
