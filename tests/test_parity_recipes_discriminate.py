@@ -120,7 +120,7 @@ def test_full_shape_attention_recipes_reject_a_short_delta(oracle, name, sparse_
         basen, ref = _attn_ref(oracle, q[:, :, rows].contiguous(), kk, v, idx[u].view(1, 1, 1, -1).contiguous(),
                                counts[u].view(1, 1, 1), base[:, :, rows].contiguous(), c, 1.0 / math.sqrt(E), 1.0)
         assert _rejects(basen, ref), (name, mode, i)
-        # the verdict on the old recipe, kept as a regression: on an N(0,1) cache a 15 % short delta passed
+        # what the earlier recipe allowed, kept as a regression: on an N(0,1) cache a 15 % short delta passed
         if mode == "delta" and name != "flux":
             unit_base = si.np_f32(recipes.attn_base(tuple(basen.shape), sparse_k, "unit", 1, CPU)).astype(np.float64)
             hidden = unit_base + 0.85 * (ref - basen)
