@@ -135,6 +135,50 @@ def test_topk_ties_and_structured_scores(cm, oracle):
     assert np.array_equal(idx.cpu().numpy(), ref_idx)
 
 
+@pytest.mark.parametrize("kind", ["constant", "two_values", "tiny_range", "denormal", "negative", "infinities",
+                                  "ascending", "descending", "spikes", "signed_zeros", "heavy_tail"])
+def test_topk_long_rows_awkward_distributions(cm, oracle, kind):
+    """Long rows whose scores give the single-pass selection nothing to hold on to: one value (every sample key
+    equal, the whole row between the pivots), two values, a range of a few ulps, denormals, negative scores,
+    infinities among the sample, sorted rows, a few spikes over zeros, zeros of both signs, a heavy tail.  With and
+    without a previous score tensor, keep fractions from one column to all but one."""
+    rng = np.random.default_rng(7)
+    R, C = 3, 70001                                     # not a multiple of 4: padded leading dimension
+    ld = -(-C // 4) * 4
+    if kind == "constant": a = np.full((R, C), 3.25, np.float32)
+    elif kind == "two_values": a = rng.choice(np.array([1.0, 2.0], np.float32), size=(R, C))
+    elif kind == "tiny_range": a = (1.0 + 1e-6 * rng.random((R, C))).astype(np.float32)
+    elif kind == "denormal": a = (1e-41 * rng.random((R, C))).astype(np.float32)
+    elif kind == "negative": a = -np.abs(rng.standard_normal((R, C))).astype(np.float32)
+    elif kind == "infinities":
+        a = rng.standard_normal((R, C)).astype(np.float32)
+        a[:, ::97] = np.inf
+        a[:, 5::131] = -np.inf
+    elif kind == "ascending": a = np.sort(rng.random((R, C)).astype(np.float32), axis=1)
+    elif kind == "descending": a = -np.sort(-rng.random((R, C)).astype(np.float32), axis=1)
+    elif kind == "spikes":
+        a = np.zeros((R, C), np.float32)
+        a[:, rng.integers(0, C, 50)] = rng.random(50).astype(np.float32)
+    elif kind == "signed_zeros": a = rng.choice(np.array([0.0, -0.0, 1e-30, -1e-30], np.float32), size=(R, C))
+    else: a = np.exp(3 * rng.standard_normal((R, C))).astype(np.float32)
+    b = rng.standard_normal((R, C)).astype(np.float32)
+
+    def padded(x):
+        full = torch.zeros((R, ld), dtype=torch.float32, device=DEV)
+        full[:, :C] = torch.from_numpy(x).to(DEV)
+        return full[:, :C]
+
+    cur, prev = padded(a), padded(b)
+    for k in (1, 17, C // 14, C // 2, C - 1):
+        for with_prev in (False, True):
+            idx = torch.full((R, k), -1, dtype=torch.int32, device=DEV)
+            counts = torch.zeros((R,), dtype=torch.int32, device=DEV)
+            cm.topk_cols(cur, prev if with_prev else None, k, idx, counts)
+            ref_idx, _ = oracle.topk_cols(a, b if with_prev else None, k)
+            assert np.array_equal(idx.cpu().numpy(), ref_idx), (kind, k, with_prev)
+            assert bool((counts == k).all())
+
+
 # --------------------------------------------------------- bit-packed masks ---
 
 @pytest.mark.parametrize("R,C,k", [
