@@ -22,6 +22,7 @@
 #include "common.h"
 
 #include <mutex>
+#include <type_traits>
 
 namespace chipmunk {
 
@@ -68,8 +69,12 @@ static int xcd_grid_size_grouped(int col_tiles, int units) {
 }
 
 
-__device__ __forceinline__ float gelu(float x, int act) {
-    if (act == CHIPMUNK_ACT_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
+// ACT is a template argument so that a tile's activations are straight-line code: with the form chosen by a
+// run-time branch inside, every element became a basic block of its own and its dozen dependent instructions
+// ran one after the other.
+template <int ACT>
+__device__ __forceinline__ float gelu(float x) {
+    if (ACT == CHIPMUNK_ACT_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
     // tanh form: 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
     float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
     return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-2.885390081777927f * u));  // v_rcp_f32: 1 ulp, the result is rounded to bf16
@@ -259,69 +264,88 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) bias_raw[nt] = bias_src[s_neuron[wn * 64 + nt * 32 + l32]];
     u32x4 old8[ITEMS];
-    if (MODE == kSparseDelta) {
+    uint16_t* cell[ITEMS];   // the thread's cells in a_cache (token clamped to the row's start where the chunk ends early)
 #pragma unroll
-        for (int n = 0; n < ITEMS; n++) {
-            const int item = tid + n * 256;
-            const int nl = item / CPR, ch = item - nl * CPR;
-            const int tok0 = row0 + ch * 8;
-            const uint16_t* arow = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + (tok0 < p.N ? tok0 : 0);
-            old8[n] = *reinterpret_cast<const u32x4*>(arow);
-        }
+    for (int n = 0; n < ITEMS; n++) {
+        const int item = tid + n * 256;
+        const int nl = item / CPR, ch = item - nl * CPR;
+        const int tok0 = row0 + ch * 8;
+        cell[n] = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + (tok0 < p.N ? tok0 : 0);
+        if (MODE == kSparseDelta) old8[n] = *reinterpret_cast<const u32x4*>(cell[n]);
     }
     lds_accesses_then_barrier();  // every wave is done with the stage buffers
     float bias[2];
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) bias[nt] = p.b1 ? bf16_bits_to_float(bias_raw[nt]) : 0.f;
+    auto activate_tile = [&](auto form) {
+        constexpr int ACT = decltype(form)::value;
 #pragma unroll
-    for (int nt = 0; nt < 2; nt++) {
-        int nl = wn * 64 + nt * 32 + l32;
+        for (int nt = 0; nt < 2; nt++) {
+            int nl = wn * 64 + nt * 32 + l32;
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++)
+            for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-            for (int rg = 0; rg < 4; rg++) {
-                int tl = wm * (BM / 2) + mt * 32 + rg * 8 + h * 4;
-                float a0 = gelu(acc[mt][nt][rg * 4 + 0] + bias[nt], p.act);
-                float a1 = gelu(acc[mt][nt][rg * 4 + 1] + bias[nt], p.act);
-                float a2 = gelu(acc[mt][nt][rg * 4 + 2] + bias[nt], p.act);
-                float a3 = gelu(acc[mt][nt][rg * 4 + 3] + bias[nt], p.act);
-                u32x2 v = {pack_bf16x2(a0, a1), pack_bf16x2(a2, a3)};
-                *reinterpret_cast<u32x2*>(smem + nl * TS + tl * 2) = v;
-            }
-    }
+                for (int rg = 0; rg < 4; rg++) {
+                    int tl = wm * (BM / 2) + mt * 32 + rg * 8 + h * 4;
+                    float a0 = gelu<ACT>(acc[mt][nt][rg * 4 + 0] + bias[nt]);
+                    float a1 = gelu<ACT>(acc[mt][nt][rg * 4 + 1] + bias[nt]);
+                    float a2 = gelu<ACT>(acc[mt][nt][rg * 4 + 2] + bias[nt]);
+                    float a3 = gelu<ACT>(acc[mt][nt][rg * 4 + 3] + bias[nt]);
+                    u32x2 v = {pack_bf16x2(a0, a1), pack_bf16x2(a2, a3)};
+                    *reinterpret_cast<u32x2*>(smem + nl * TS + tl * 2) = v;
+                }
+        }
+    };
+    if (p.act == CHIPMUNK_ACT_GELU_ERF) activate_tile(std::integral_constant<int, CHIPMUNK_ACT_GELU_ERF>{});
+    else activate_tile(std::integral_constant<int, CHIPMUNK_ACT_GELU_TANH>{});
     lds_accesses_then_barrier();
+    // The cells are handled in three sweeps (read the transposed tile, form the deltas, store) of straight-line
+    // code: in one loop with a branch per cell every cell waited for its own LDS reads, and the compiler, which
+    // counts a wait as if no store had been issued on the way, made it wait for the stores of the cells before.
+    u32x4 a8[ITEMS];
 #pragma unroll
     for (int n = 0; n < ITEMS; n++) {
         const int item = tid + n * 256;
-        int nl = item / CPR, ch = item - nl * CPR;
-        int s = col0 + nl;
-        int tok0 = row0 + ch * 8;
-        int nvalid = min(8, p.N - tok0);
-        if (nvalid <= 0 || s >= count) {  // no such tokens, or a padding row of the contraction: it must read as zero in GEMM2
-            if (MODE == kSparseDelta && s < p.k_pad)
-                *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = u32x4{0, 0, 0, 0};
-            continue;
-        }
-        u32x4 a8 = *reinterpret_cast<const u32x4*>(smem + nl * TS + ch * 16);
-        uint16_t* arow = p.a_cache + ((int64_t)b * p.F + s_neuron[nl]) * p.a_ld + tok0;
-        if (MODE == kSparseDelta && p.act_t) {   // deferred write-back: one coalesced store, whole cell
-            *reinterpret_cast<u32x4*>(p.act_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = a8;
-        } else if (nvalid == 8) {
-            *reinterpret_cast<u32x4*>(arow) = a8;
-        } else {  // the cells past N in the last chunk stay as they are
-            for (int e = 0; e < nvalid; e++) arow[e] = (uint16_t)(a8[e >> 1] >> (16 * (e & 1)));
-        }
-        if (MODE == kDenseAct) continue;
-        u32x4 d8;
+        const int nl = item / CPR, ch = item - nl * CPR;
+        a8[n] = *reinterpret_cast<const u32x4*>(smem + nl * TS + ch * 16);
+    }
+    if (MODE == kSparseDelta) {
+        // the cached activations, requested before the activation arithmetic, are taken as arrived in one wait
 #pragma unroll
-        for (int e2 = 0; e2 < 4; e2++) {
-            float dlo = bf16_bits_to_float(a8[e2] & 0xffffu) - bf16_bits_to_float(old8[n][e2] & 0xffffu);
-            float dhi = bf16_bits_to_float(a8[e2] >> 16) - bf16_bits_to_float(old8[n][e2] >> 16);
-            if (2 * e2 >= nvalid) dlo = 0.f;
-            if (2 * e2 + 1 >= nvalid) dhi = 0.f;
-            d8[e2] = pack_bf16x2(dlo, dhi);
+        for (int n = 0; n < ITEMS; n++) asm volatile("" ::"v"(old8[n]), "v"(a8[n]));
+        uint16_t* dunit = p.delta_t + (int64_t)unit * p.k_pad * BM;
+#pragma unroll
+        for (int n = 0; n < ITEMS; n++) {
+            const int item = tid + n * 256;
+            const int nl = item / CPR, ch = item - nl * CPR;
+            const int s = col0 + nl;
+            // tokens past N and padding rows of the contraction must read as zero in GEMM2
+            const int nvalid = s < count ? min(8, p.N - (row0 + ch * 8)) : 0;
+            u32x4 d8;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; e2++) {
+                float dlo = bf16_bits_to_float(a8[n][e2] & 0xffffu) - bf16_bits_to_float(old8[n][e2] & 0xffffu);
+                float dhi = bf16_bits_to_float(a8[n][e2] >> 16) - bf16_bits_to_float(old8[n][e2] >> 16);
+                if (2 * e2 >= nvalid) dlo = 0.f;
+                if (2 * e2 + 1 >= nvalid) dhi = 0.f;
+                d8[e2] = pack_bf16x2(dlo, dhi);
+            }
+            if (s < p.k_pad) *reinterpret_cast<u32x4*>(dunit + (s * BM + ch * 8)) = d8;
         }
-        *reinterpret_cast<u32x4*>(p.delta_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = d8;
+    }
+#pragma unroll
+    for (int n = 0; n < ITEMS; n++) {
+        const int item = tid + n * 256;
+        const int nl = item / CPR, ch = item - nl * CPR;
+        const int s = col0 + nl;
+        const int nvalid = s < count ? min(8, p.N - (row0 + ch * 8)) : 0;
+        if (MODE == kSparseDelta && p.act_t) {   // deferred write-back: one coalesced store, whole cell
+            if (nvalid > 0) *reinterpret_cast<u32x4*>(p.act_t + ((int64_t)unit * p.k_pad + s) * BM + ch * 8) = a8[n];
+        } else if (nvalid == 8) {
+            *reinterpret_cast<u32x4*>(cell[n]) = a8[n];
+        } else {  // the cells past N in the last chunk stay as they are
+            for (int e = 0; e < nvalid; e++) cell[n][e] = (uint16_t)(a8[n][e >> 1] >> (16 * (e & 1)));
+        }
     }
 }
 
@@ -561,6 +585,15 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
                     }
         }
         lds_accesses_then_barrier();
+        if (half == 0) {
+            // Every value requested above is taken as arrived before the first store, in one wait.  The stores sit
+            // in branches, so the waits the compiler counts per item assume that none was issued: left to the
+            // loop, the second half's items would wait for the first half's stores.
+#pragma unroll
+            for (int hh = 0; hh < 2; hh++)
+#pragma unroll
+                for (int n = 0; n < ITEMS; n++) asm volatile("" ::"v"(old[hh][n]));
+        }
 #pragma unroll
         for (int n = 0; n < ITEMS; n++) {
             const int item = tid + n * 256;
