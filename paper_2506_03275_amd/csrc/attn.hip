@@ -273,17 +273,21 @@ __device__ __forceinline__ void attn_weights_and_pv(AttnState<E, NQB>& st, const
 constexpr int kBlockColumns = CHIPMUNK_ATTN_BLOCK_COLUMNS;   // key columns per entry of a block list
 static_assert(kBlockColumns % (kTilesPerStep * kTileRows) == 0, "a step never straddles two blocks");
 
-// What the kernel walks.  kColumnList: the unit's list of columns (or, without a list, every column: dense).
+// What the kernel walks.  kColumnList: the unit's list of columns.  kEveryColumn: no list, every column (dense).
 // kFusedDense: every column, and the column sums of Alg. 4 are formed from the same score tiles.  kBlockList: the
 // unit's list names blocks of kBlockColumns consecutive columns (the [c, 128] block sparsity of Table 2); the list
 // positions are the blocks' columns in order, so the rows of a step are one contiguous run of K and V.
-enum AttnMode { kColumnList = 0, kFusedDense = 1, kBlockList = 2 };
+enum AttnMode { kColumnList = 0, kFusedDense = 1, kBlockList = 2, kEveryColumn = 3 };
 
 // NWAVES waves per workgroup, each owning NQB blocks of 16 queries: c = 16 * NQB * NWAVES.
 template <int E, int NQB, int NWAVES, int MODE = kColumnList>
 __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_delta_kernel(AttnParams p) {
     constexpr bool FUSED = MODE == kFusedDense;
     constexpr bool BLOCKS = MODE == kBlockList;
+    // Every column in order: the columns are the list positions.  A mode of its own and not a null list inside
+    // kColumnList: there the branch on the pointer put a wait for all memory behind each step's tile requests (the
+    // compiler guards the registers that the other branch loads the column numbers into).
+    constexpr bool NOLIST = FUSED || MODE == kEveryColumn;
     constexpr int ROWB = E * 2;           // bytes per K/V row
     constexpr int CH = ROWB / 16;         // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // rows covered by one wave-wide 16-byte load
@@ -415,7 +419,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     // at or beyond `count` reads as column 0: a valid row, whose scores the last tile masks.
     const i32x4 kbuf = raw_buffer_words(kh, (uint32_t)p.N * ROWB);
     const i32x4 vbuf = raw_buffer_words(vh, (uint32_t)p.N * ROWB);
-    const int32_t* idxg = p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
+    const int32_t* idxg = !NOLIST && p.idx ? p.idx + unit * (int64_t)p.k_stride : nullptr;
     // two views of the unit's list: its whole row (positions below k_stride: the vector loads of the steps that lie
     // inside the list) and the part below count (a position at or beyond count reads as 0: the list's last step)
     const __amdgpu_buffer_rsrc_t ibuf_row = raw_buffer(idxg, idxg ? (uint32_t)p.k_stride * 4u : 0u);
@@ -434,31 +438,25 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     if constexpr (MODE == kColumnList) {
         const int last_pos = (ntiles / kTilesPerStep - 1) * (kTilesPerStep * kTileRows) + next_pos;
 #pragma unroll
-        for (int j = 0; j < RPL; j++)
-            colt[j] = idxg ? __builtin_amdgcn_raw_buffer_load_b32(ibuf, (last_pos + j) * 4, 0, 0) : min(last_pos + j, p.N - 1);
+        for (int j = 0; j < RPL; j++) colt[j] = __builtin_amdgcn_raw_buffer_load_b32(ibuf, (last_pos + j) * 4, 0, 0);
     }
     int blockv = 0;                               // BLOCKS: the block that holds the next step to gather (the same in every lane)
     int block_now = 0, block_next = 0;            // BLOCKS: first column of the block of the step in work / of the next step
     auto load_cols = [&]() {
-        if constexpr (FUSED) return;   // gather_offsets forms the columns from the positions
+        if constexpr (NOLIST) return;  // gather_offsets forms the columns from the positions
         if constexpr (BLOCKS) {        // one list entry serves kBlockColumns positions; past the list's end it reads as block 0
             blockv = __builtin_amdgcn_raw_buffer_load_b32(ibuf, (next_pos / kBlockColumns) * 4, 0, 0);
             next_pos += kTilesPerStep * kTileRows;
             return;
         }
-        if (idxg) {
-            if constexpr (RPL == 4) {
-                const u32x4 c4 = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ibuf_row, next_pos * 4, 0, 0));
+        if constexpr (RPL == 4) {
+            const u32x4 c4 = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ibuf_row, next_pos * 4, 0, 0));
 #pragma unroll
-                for (int j = 0; j < RPL; j++) colv[j] = (int)c4[j];
-            } else {
-                const u32x2 c2 = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(ibuf_row, next_pos * 4, 0, 0));
+            for (int j = 0; j < RPL; j++) colv[j] = (int)c4[j];
+        } else {
+            const u32x2 c2 = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(ibuf_row, next_pos * 4, 0, 0));
 #pragma unroll
-                for (int j = 0; j < RPL; j++) colv[j] = (int)c2[j];
-            }
-        } else {  // dense: column = position
-#pragma unroll
-            for (int j = 0; j < RPL; j++) colv[j] = min(next_pos + j, p.N - 1);
+            for (int j = 0; j < RPL; j++) colv[j] = (int)c2[j];
         }
         next_pos += kTilesPerStep * kTileRows;
     };
@@ -474,7 +472,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
 #pragma unroll
             for (int i = 0; i < NI; i++) {
                 int col;
-                if constexpr (FUSED) col = min(gather_pos + s * NI + i, p.N - 1);   // always dense: column = position
+                if constexpr (NOLIST) col = min(gather_pos + s * NI + i, p.N - 1);   // column = position
                 else if constexpr (BLOCKS) col = min(blockv * kBlockColumns + (gather_pos % kBlockColumns) + s * NI + i, p.N - 1);
                 else col = last ? colt[s * NI + i] : colv[s * NI + i];
                 goff[s][i] = (uint32_t)col * ROWB + chunk_off[i];
@@ -548,6 +546,18 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
         if (t + kTilesPerStep >= ntiles) break;
         step(std::integral_constant<int, 1>{}, t + kTilesPerStep);
     }
+    // The base rows that the results are merged with are requested here, for every query block at once and in front
+    // of the wait for the last step's transfers: one round trip for all of it.  Without a branch: a query row that
+    // does not exist reads the chunk's last row, a call without base reads the output buffer; neither value is used.
+    const uint16_t* base_src = baseh ? baseh : outh;
+    u32x2 bv[NQB][E / 16];
+#pragma unroll
+    for (int qb = 0; qb < NQB; qb++) {
+        int qrow = (w * NQB + qb) * 16 + l16;
+        const int64_t row_off = (int64_t)(row0 + min(qrow, rows_valid - 1)) * E + 4 * g;
+#pragma unroll
+        for (int eb = 0; eb < E / 16; eb++) bv[qb][eb] = *reinterpret_cast<const u32x2*>(base_src + row_off + eb * 16);
+    }
     wait_all_memory();  // the last step's transfers into the unused half must have landed before the wave may end
     if (FUSED) {
         __syncthreads();  // the last step's partial sums are complete
@@ -555,19 +565,12 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
     }
 
     if (!wave_active) return;
-    // The base rows of a query block are requested together, before the block's results are stored (one round trip
-    // per block, not one per store), and without a branch: a query row that does not exist reads the chunk's last
-    // row, a call without base reads the output buffer; neither value is used.
-    const uint16_t* base_src = baseh ? baseh : outh;
 #pragma unroll
     for (int qb = 0; qb < NQB; qb++) {
         float ltot = st.L[qb][0];
         float f = p.o_scale / ltot;
         int qrow = (w * NQB + qb) * 16 + l16;
         const int64_t row_off = (int64_t)(row0 + min(qrow, rows_valid - 1)) * E + 4 * g;
-        u32x2 bv[E / 16];
-#pragma unroll
-        for (int eb = 0; eb < E / 16; eb++) bv[eb] = *reinterpret_cast<const u32x2*>(base_src + row_off + eb * 16);
         if (qrow < rows_valid) {
             if (p.row_m && g == 0) {
                 p.row_m[bh * p.N + row0 + qrow] = -st.negm[qb][0] * (p.sl2 * 0.6931471805599453f);
@@ -575,7 +578,7 @@ __global__ __launch_bounds__(64 * NWAVES, NWAVES == 4 ? 2 : 1) void attn_sparse_
             }
 #pragma unroll
             for (int eb = 0; eb < E / 16; eb++) {
-                u32x2 b = baseh ? bv[eb] : u32x2{0, 0};
+                u32x2 b = baseh ? bv[qb][eb] : u32x2{0, 0};
                 float o0 = bf16_bits_to_float(b[0] & 0xffffu) + f * st.O[eb][qb][0];
                 float o1 = bf16_bits_to_float(b[0] >> 16) + f * st.O[eb][qb][1];
                 float o2 = bf16_bits_to_float(b[1] & 0xffffu) + f * st.O[eb][qb][2];
@@ -722,6 +725,12 @@ static int32_t launch_attn_variant(const AttnParams& p, int64_t units, hipStream
 }
 
 static int32_t launch_attn(const AttnParams& p, int E, int64_t units, hipStream_t s) {
+    if (!p.idx) {
+        if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4, kEveryColumn>(p, units, s);
+        if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4, kEveryColumn>(p, units, s);
+        if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4, kEveryColumn>(p, units, s);
+        return launch_attn_variant<64, 2, 4, kEveryColumn>(p, units, s);
+    }
     if (E == 128 && p.c == 192) return launch_attn_variant<128, 3, 4>(p, units, s);
     if (E == 128 && p.c == 128) return launch_attn_variant<128, 2, 4>(p, units, s);
     if (E == 64 && p.c == 192) return launch_attn_variant<64, 3, 4>(p, units, s);
