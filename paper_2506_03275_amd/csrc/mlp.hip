@@ -594,18 +594,25 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm2_kernel(Gemm2Params p) {
 #pragma unroll
                 for (int n = 0; n < ITEMS; n++) asm volatile("" ::"v"(old[hh][n]));
         }
+        // two sweeps of straight-line code (read the staged tile, then merge and store): in one loop with the
+        // store's branch inside, every item waited for its own LDS read
+        f32x4 a4[ITEMS];
+#pragma unroll
+        for (int n = 0; n < ITEMS; n++) {
+            const int item = tid + n * 256;
+            a4[n] = *reinterpret_cast<const f32x4*>(smem + (item >> 5) * CS + (item & 31) * 16);
+        }
 #pragma unroll
         for (int n = 0; n < ITEMS; n++) {
             const int item = tid + n * 256;
             const int tl = item >> 5, ch = item & 31;
             const int tok = row0 + half * (BM / 2) + tl;
-            f32x4 a4 = *reinterpret_cast<const f32x4*>(smem + tl * CS + ch * 16);
             uint16_t* orow = p.o + ((int64_t)b * p.N + tok) * p.D + d0 + ch * 4;
             const u32x2 o2 = add_nothing ? u32x2{0, 0} : old[half][n];
-            float o0 = bf16_bits_to_float(o2[0] & 0xffffu) + a4[0];
-            float o1 = bf16_bits_to_float(o2[0] >> 16) + a4[1];
-            float o2f = bf16_bits_to_float(o2[1] & 0xffffu) + a4[2];
-            float o3 = bf16_bits_to_float(o2[1] >> 16) + a4[3];
+            float o0 = bf16_bits_to_float(o2[0] & 0xffffu) + a4[n][0];
+            float o1 = bf16_bits_to_float(o2[0] >> 16) + a4[n][1];
+            float o2f = bf16_bits_to_float(o2[1] & 0xffffu) + a4[n][2];
+            float o3 = bf16_bits_to_float(o2[1] >> 16) + a4[n][3];
             u32x2 res = {pack_bf16x2(o0, o1), pack_bf16x2(o2f, o3)};
             if (tok < p.N) *reinterpret_cast<u32x2*>(orow) = res;
         }
