@@ -50,11 +50,11 @@ CALIBRATION_COPY_BYTES = 256 << 20
 # attention kernel's sources are the ones the counters were taken on (ATTN_SOURCES_MEASURED is the
 # digest attn_sources_digest() gave then); after any change to them `traffic` is null until the
 # counters are taken again.
-ATTN_SOURCES_MEASURED = "47982a30283767d1"
-MEASURED_ATTN_TRAFFIC_BYTES = {   # read factor * FETCH_SIZE KiB + write factor * WRITE_SIZE KiB (mean of the timed launches)
-    "flux": 2.0 * 66917 * 1024 + 1.0 * 27648 * 1024,
-    "hunyuan": 2.0 * 12450384 * 1024 + 1.0 * 692762 * 1024,
-    "wan": 2.0 * 9257895 * 1024 + 1.0 * 756036 * 1024,
+ATTN_SOURCES_MEASURED = "3b0c7ebaf0dd1455"
+MEASURED_ATTN_TRAFFIC_BYTES = {   # read factor * FETCH_SIZE KiB + write factor * WRITE_SIZE KiB (mean of the last four launches)
+    "flux": 2.0 * 66920 * 1024 + 1.0 * 27648 * 1024,
+    "hunyuan": 2.0 * 12442452 * 1024 + 1.0 * 692737 * 1024,
+    "wan": 2.0 * 9309438 * 1024 + 1.0 * 756001 * 1024,
 }
 
 
