@@ -407,7 +407,8 @@ def test_attn_all_columns_equals_dense_and_cache_roundtrip(cm, oracle):
     assert float(np.abs(si.np_f32(again) - ref).max()) <= bound
 
 
-@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (1, 2, 700, 128, 192)])
+@pytest.mark.parametrize("B,H,N,E,c", [(1, 2, 1024, 64, 128), (1, 2, 700, 128, 192), (1, 2, 520, 64, 192),
+                                       (2, 1, 600, 128, 128)])   # the four instantiations of the every-column mode
 def test_attn_dense_with_colsum_parity(cm, oracle, B, H, N, E, c):
     (q, kk, v), _, _ = si.attn_steps(B, H, N, E, 5, DEV)
     scale = 1.0 / math.sqrt(E)
