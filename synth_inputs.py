@@ -133,7 +133,7 @@ def uniform_indices(R, C, k, seed, device="cpu", k_stride=None):
     for r0 in range(0, R, rows_per):
         r1 = min(R, r0 + rows_per)
         keys = torch.rand((r1 - r0, C), generator=g, device=device)
-        sel = keys.argsort(dim=1)[:, :k].sort(dim=1).values
+        sel = keys.argsort(dim=1, stable=True)[:, :k].sort(dim=1).values
         idx[r0:r1, :k] = sel.to(torch.int32)
     counts = torch.full((R,), k, dtype=torch.int32, device=device)
     return idx, counts
@@ -143,7 +143,7 @@ def distinct_scores(R, C, seed, device="cpu"):
     """[R,C] float32 with no two equal entries in a row (a shuffled arithmetic grid plus jitter)."""
     g = generator(seed + 5000003, device)
     keys = torch.rand((R, C), generator=g, device=device)
-    rank = keys.argsort(dim=1).argsort(dim=1).to(torch.float32)
+    rank = keys.argsort(dim=1, stable=True).argsort(dim=1, stable=True).to(torch.float32)
     return (rank - (C - 1) / 2.0) / 64.0
 
 
@@ -196,7 +196,7 @@ def block_indices(R, C, k, block, seed, device="cpu"):
     n_blocks_total = -(-C // block)
     n_pick = min(n_blocks_total, -(-k // block) + 1)
     keys = torch.rand((R, n_blocks_total), generator=g, device=device)
-    picked = keys.argsort(dim=1)[:, :n_pick].sort(dim=1).values                      # [R, n_pick] block numbers
+    picked = keys.argsort(dim=1, stable=True)[:, :n_pick].sort(dim=1).values                      # [R, n_pick] block numbers
     cols = (picked.unsqueeze(-1) * block + torch.arange(block, device=device)).reshape(R, -1)
     cols = torch.where(cols < C, cols, torch.full_like(cols, C))                     # the last block may be ragged
     cols = cols.sort(dim=1).values[:, :k]

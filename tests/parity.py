@@ -72,7 +72,7 @@ def attn_indices(units, N, k, seed, device, ragged=False, order="ascending"):
     idx, counts = si.uniform_indices(units, N, k, seed, device)
     if order in ("shuffled", "duplicates"):
         g = si.generator(seed + 31, device)
-        shuffle = torch.rand((units, k), generator=g, device=device).argsort(dim=1)
+        shuffle = torch.rand((units, k), generator=g, device=device).argsort(dim=1, stable=True)
         idx = torch.gather(idx, 1, shuffle)
     if order == "duplicates" and k >= 3:
         idx[:, k - k // 3:] = idx[:, :k // 3]
@@ -110,7 +110,7 @@ def attn_block_lists(units, N, n_blocks, seed, device, ragged=False, block=128):
     total = -(-N // block)
     g = si.generator(seed + 6000003, device)
     keys = torch.rand((units, total), generator=g, device=device)
-    blocks = keys.argsort(dim=1)[:, :n_blocks].sort(dim=1).values.to(torch.int32).contiguous()
+    blocks = keys.argsort(dim=1, stable=True)[:, :n_blocks].sort(dim=1).values.to(torch.int32).contiguous()
     counts = torch.full((units,), n_blocks, dtype=torch.int32, device=device)
     if ragged:
         counts[0] = 0
