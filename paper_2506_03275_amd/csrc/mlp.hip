@@ -101,10 +101,14 @@ struct Gemm1Params {
 
 // NS tile buffers: NS - 1 contraction steps are in flight while one is consumed.  The column-sparse and the dense
 // form run with three (120 KB, one workgroup per CU): measured against two buffers and two workgroups per CU,
-// which keep the same number of bytes in flight, the MLP delta takes 11 % less time and the dense MLP 9 % less.  The scores GEMM (few,
-// short workgroups) keeps two.
-template <int BM, int MODE, int NS>
-__global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
+// which keep the same number of bytes in flight, the MLP delta takes 11 % less time and the dense MLP 9 % less.
+// The scores GEMM (few, short workgroups) keeps two.
+template <int BM, int MODE, int NS, bool LOADER>
+__global__ __launch_bounds__(LOADER ? 320 : 256, LOADER ? 1 : 2) void mlp_gemm1_kernel(Gemm1Params p) {
+    // LOADER: a fifth wave issues every tile transfer of the workgroup; the four product waves issue none.  A wave
+    // issues in order, so a transfer that waits for room in the memory pipeline holds up the products behind it.
+    // The loader wave takes part in every barrier of the kernel and in nothing else.
+    constexpr int VW = LOADER ? 4 : 1;             // waves whose share of the transfers one issuing wave carries
     constexpr int MT = BM / 64;                    // 32-row MFMA tiles per wave (wave tile = BM/2 x 64)
     constexpr int XT = BM * 128;                   // bytes of the x tile  [BM][64] bf16
     constexpr int WT = kBN * 128;                  // bytes of the w1 tile [128][64] bf16
@@ -116,6 +120,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     __shared__ int32_t s_neuron[kBN];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const bool loader = LOADER && w == 4;          // wave-uniform
     const int wm = w >> 1, wn = w & 1;
     const int l32 = lane & 31, h = lane >> 5;
 
@@ -147,32 +152,37 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     __syncthreads();
 
     // per-lane source offsets (bytes) of the asynchronous tile loads; the K offset is uniform
-    uint32_t xoff[NIX], woff[NIW];
+    uint32_t xoff[NIX * VW], woff[NIW * VW];
 #pragma unroll
-    for (int i = 0; i < NIX; i++) {
-        int row = (i * 4 + w) * 8 + (lane >> 3);
-        int chunk16 = (lane & 7) ^ ((row >> 1) & 7);
-        int tok = min(row0 + row, p.N - 1);
-        xoff[i] = (uint32_t)tok * (uint32_t)(p.ldx * 2) + chunk16 * 16;
-    }
+    for (int i = 0; i < NIX; i++)
 #pragma unroll
-    for (int i = 0; i < NIW; i++) {
-        int row = (i * 4 + w) * 8 + (lane >> 3);
-        int chunk16 = (lane & 7) ^ ((row >> 1) & 7);
-        woff[i] = (uint32_t)s_neuron[row] * (uint32_t)(p.D * 2) + chunk16 * 16;
-    }
+        for (int v = 0; v < VW; v++) {
+            int row = (i * 4 + (LOADER ? v : w)) * 8 + (lane >> 3);
+            int chunk16 = (lane & 7) ^ ((row >> 1) & 7);
+            int tok = min(row0 + row, p.N - 1);
+            xoff[i * VW + v] = (uint32_t)tok * (uint32_t)(p.ldx * 2) + chunk16 * 16;
+        }
+#pragma unroll
+    for (int i = 0; i < NIW; i++)
+#pragma unroll
+        for (int v = 0; v < VW; v++) {
+            int row = (i * 4 + (LOADER ? v : w)) * 8 + (lane >> 3);
+            int chunk16 = (lane & 7) ^ ((row >> 1) & 7);
+            woff[i * VW + v] = (uint32_t)s_neuron[row] * (uint32_t)(p.D * 2) + chunk16 * 16;
+        }
     const uint16_t* xb = p.x + (int64_t)b * p.N * p.ldx;
-    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (uint32_t)w * 1024u);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem) + (LOADER ? 0u : (uint32_t)w * 1024u));
 
-    // One of the NIX + NIW transfers that bring contraction step kt into buffer `stage`.  The main loop issues them
-    // one by one between its products: requested in one burst after the barrier they queue up in the memory
-    // pipeline while the wave issues nothing else.
-    auto issue_piece = [&](int kt, int stage, int j) {
-        if (j < NIX) {
-            load_global_to_lds_16B(xb + kt * kBK, xoff[j], lds0 + stage * STAGE + j * 4096);
+    // One of the transfers that bring contraction step kt into buffer `stage`.  Without a loader wave the main loop
+    // issues a wave's NIX + NIW two by two between its products: requested in one burst after the barrier they
+    // queue up in the memory pipeline while the wave issues nothing else.
+    auto issue_piece = [&](int kt, int stage, int j) {   // j < (NIX + NIW) * VW; piece (i, v) = (j / VW, j % VW)
+        const int i = j / VW, v = j % VW;
+        if (i < NIX) {
+            load_global_to_lds_16B(xb + kt * kBK, xoff[j], lds0 + stage * STAGE + i * 4096 + v * 1024);
         } else {
             const uint16_t* ws = p.w1 + (kt * kBK) % p.D;   // the scores GEMM walks w1's row twice (hi and lo halves of A)
-            load_global_to_lds_16B(ws, woff[j - NIX], lds0 + stage * STAGE + XT + (j - NIX) * 4096);
+            load_global_to_lds_16B(ws, woff[j - NIX * VW], lds0 + stage * STAGE + XT + (i - NIX) * 4096 + v * 1024);
         }
     };
     static_assert(NIX + NIW <= 4 * MT, "one transfer per pair of products");
@@ -194,11 +204,29 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
     const int kt_begin = MODE == kPlainF32 ? (int)((int64_t)ktiles_all * piece / p.ksplit) : 0;
     const int kt_end = MODE == kPlainF32 ? (int)((int64_t)ktiles_all * (piece + 1) / p.ksplit) : ktiles_all;
     constexpr int NP = NIX + NIW;
+    if (!LOADER || loader) {
 #pragma unroll
-    for (int st = 0; st < NS - 1; st++)
+        for (int st = 0; st < NS - 1; st++)
 #pragma unroll
-        for (int j = 0; j < NP; j++) issue_piece(min(kt_begin + st, max(kt_end - 1, kt_begin)), st, j);
+            for (int j = 0; j < NP * VW; j++) issue_piece(min(kt_begin + st, max(kt_end - 1, kt_begin)), st, j);
+    }
     int stage = 0;
+    static_assert((NS - 2) * NP * VW < 64, "the transfer counter has six bits");
+    if (loader) {
+        for (int kt = kt_begin; kt < kt_end; kt++) {
+            wait_vmem_at_most<(NS - 2) * NP * VW>();
+            __syncthreads();
+            const int kt_next = min(kt + NS - 1, kt_end - 1);
+            const int fill = (stage + NS - 1) % NS;
+#pragma unroll
+            for (int j = 0; j < NP * VW; j++) issue_piece(kt_next, fill, j);
+            stage = stage + 1 == NS ? 0 : stage + 1;
+        }
+        wait_all_memory();                 // the transfers must have landed before the epilogue reuses the buffers
+        lds_accesses_then_barrier();       // the two barriers of the epilogue
+        lds_accesses_then_barrier();
+        return;
+    }
     for (int kt = kt_begin; kt < kt_end; kt++) {
         // The transfers complete in the order they were issued: this step's tiles have landed when no more than
         // the pieces of the NS - 2 younger steps are outstanding.
@@ -208,19 +236,32 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm1_kernel(Gemm1Params p) {
         const int kt_next = min(kt + NS - 1, kt_end - 1);
         const int fill = (stage + NS - 1) % NS;    // the buffer the step before this one has just left
         const uint8_t* sb = smem + stage * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            bf16x8 bop[2];
+        // The operands of contraction sub-step ks + 1 are requested ahead of the products of sub-step ks (two
+        // register sets): with one wave per SIMD nothing else covers the LDS latency between a read and its product.
+        bf16x8 aop[2][MT], bop[2][2];
+        auto read_operands = [&](int ks, int set) {
 #pragma unroll
             for (int nt = 0; nt < 2; nt++)
-                bop[nt] = *reinterpret_cast<const bf16x8*>(sb + nt * 32 * 128 + (boff ^ (32 * ks)));
+                bop[set][nt] = *reinterpret_cast<const bf16x8*>(sb + nt * 32 * 128 + (boff ^ (32 * ks)));
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+                aop[set][mt] = *reinterpret_cast<const bf16x8*>(sb + mt * 32 * 128 + (aoff ^ (32 * ks)));
+        };
+        read_operands(0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, MT + 2, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            if (ks + 1 < 4) {
+                read_operands(ks + 1, (ks + 1) & 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, MT + 2, 0);   // the reads lead the block
+            }
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
-                bf16x8 aop = *reinterpret_cast<const bf16x8*>(sb + mt * 32 * 128 + (aoff ^ (32 * ks)));
 #pragma unroll
                 for (int nt = 0; nt < 2; nt++)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nt], acc[mt][nt], 0, 0, 0);
-                {
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks & 1][mt], bop[ks & 1][nt], acc[mt][nt], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                if (!LOADER) {
                     const int slot = ks * MT + mt;
                     if (2 * slot < NP) issue_piece(kt_next, fill, 2 * slot);
                     if (2 * slot + 1 < NP) issue_piece(kt_next, fill, 2 * slot + 1);
@@ -681,15 +722,16 @@ static int32_t launch_gemm1(Gemm1Params p, int col_tiles, int units, hipStream_t
     p.col_tiles = col_tiles;
     p.units = units;
     constexpr int NS = MODE == kPlainF32 ? 2 : 3;
+    constexpr bool LOADER = MODE != kPlainF32;
     constexpr int lds = NS * (BM * 128 + kBN * 128);
     // set at every launch: the attribute is kept per device (a flag remembered here would not be)
-    if (hipFuncSetAttribute((const void*)mlp_gemm1_kernel<BM, MODE, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+    if (hipFuncSetAttribute((const void*)mlp_gemm1_kernel<BM, MODE, NS, LOADER>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
         hipSuccess)
         return CHIPMUNK_ERR_LAUNCH;
     const int grid = MODE == kPlainF32 ? col_tiles * units * p.ksplit
                      : MODE == kDenseAct ? xcd_grid_size_grouped(col_tiles, units)
                                          : xcd_grid_size(col_tiles, units);
-    hipLaunchKernelGGL((mlp_gemm1_kernel<BM, MODE, NS>), dim3(grid), dim3(256), lds, s, p);
+    hipLaunchKernelGGL((mlp_gemm1_kernel<BM, MODE, NS, LOADER>), dim3(grid), dim3(LOADER ? 320 : 256), lds, s, p);
     return launch_status();
 }
 
