@@ -51,10 +51,10 @@ CALIBRATION_COPY_BYTES = 256 << 20
 # digest attn_sources_digest() gave then); after any change to them `traffic` is null until the
 # counters are taken again.
 ATTN_SOURCES_MEASURED = "3b0c7ebaf0dd1455"
-MEASURED_ATTN_TRAFFIC_BYTES = {   # read factor * FETCH_SIZE KiB + write factor * WRITE_SIZE KiB (mean of the last four launches)
-    "flux": 2.0 * 66920 * 1024 + 1.0 * 27648 * 1024,
-    "hunyuan": 2.0 * 12442452 * 1024 + 1.0 * 692737 * 1024,
-    "wan": 2.0 * 9309438 * 1024 + 1.0 * 756001 * 1024,
+MEASURED_ATTN_TRAFFIC_BYTES = {   # read factor * FETCH_SIZE KiB + write factor * WRITE_SIZE KiB (mean of the last four launches of the counter runs)
+    "flux": 2.0 * 66913 * 1024 + 1.0 * 27648 * 1024,
+    "hunyuan": 2.0 * 12480026 * 1024 + 1.0 * 692736 * 1024,
+    "wan": 2.0 * 9191464 * 1024 + 1.0 * 756001 * 1024,
 }
 
 
